@@ -1,0 +1,125 @@
+/*
+ * moe.h - C ABI of the single-GPU MoE-layer forward for AMD MI355X (gfx950).
+ *
+ * The layer is the one the paper serves (Section 2.2): a gating network plus E
+ * expert networks; the gate routes every token to k experts, a "scatter" brings
+ * tokens to their experts, the experts run, and a "gather" collects and reorders
+ * their outputs:   y[t] = sum_{j<k} g_j(x[t]) * E_{idx[t,j]}(x[t]).
+ * On one GPU the scatter is a permutation of token rows into expert-contiguous
+ * order and the gather is its weighted inverse.  The per-expert token counts the
+ * dispatch produces are the paper's expert load W_l (Sections 3.3 and 4.1), the
+ * statistic its predictor, scaler and placer consume.
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers into memory the caller owns; the
+ *     library never allocates, frees or keeps them.  `shape` is a HOST pointer.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work on it; they never synchronise the host.
+ *   - Tensors are dense row-major.  `dtype` selects the storage type of x, all
+ *     weights, x_perm, h, y_perm and y: MOE_F32 (IEEE float) or MOE_BF16
+ *     (bfloat16, round-to-nearest-even on every store).  Accumulation is fp32
+ *     (fp64 where noted).  Row byte sizes d*b and F*b must be multiples of 16 and
+ *     every pointer 16-byte aligned.
+ *   - Return value: MOE_OK or a negative moe_status_t; nothing is thrown and
+ *     nothing aborts.  Arguments are validated on the host before any launch; on
+ *     error no work has been enqueued.  T == 0 is a valid no-op.
+ *   - Non-finite inputs and expert indices outside [0,E) give unspecified values
+ *     (never out-of-bounds accesses).
+ *   - Limits: 1 <= k <= E <= 256, k <= 64, T*k < 2^31.
+ */
+#ifndef MOE_GFX950_H
+#define MOE_GFX950_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype_t;
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1, /* null pointer, bad shape, misaligned pointer        */
+  MOE_ERR_UNSUPPORTED = -2, /* shape outside the documented limits                */
+  MOE_ERR_WORKSPACE = -3,   /* workspace smaller than moe_workspace_bytes()       */
+  MOE_ERR_HIP = -4          /* a HIP runtime call failed (launch error)           */
+} moe_status_t;
+
+typedef struct {
+  int32_t T;      /* tokens                                                       */
+  int32_t d;      /* hidden size                                                  */
+  int32_t E;      /* experts                                                      */
+  int32_t k;      /* experts activated per token                                  */
+  int32_t F;      /* SwiGLU width of one expert                                   */
+  int32_t dtype;  /* moe_dtype_t                                                  */
+  int32_t renorm; /* 1: the k routing weights of a token are rescaled to sum to 1 */
+} moe_shape_t;
+
+/* Bytes of device workspace moe_count_and_permute needs for this shape. */
+int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes);
+
+/*
+ * Gate + routing (Section 2.2: "the gating network routes tokens to specific
+ * experts"; the gate is a bias-free d x E linear map, Sections 5 and 6.6).
+ *   score[t,e] = sum_i x[t,i] * w_gate[e,i]  (+ gate_bias[e] if given), as fp32
+ *   topk_idx[t,:] = the k experts with the largest score, descending; equal
+ *                   scores go to the lowest expert index
+ *   topk_w[t,j]   = softmax_E(score[t,:])[topk_idx[t,j]], divided by their sum
+ *                   over j when shape->renorm != 0
+ * x [T,d], w_gate [E,d] in `dtype`; gate_bias [E] fp32 or NULL; topk_idx [T,k]
+ * int32; topk_w [T,k] fp32; scores_out [T,E] fp32 or NULL (the scores the
+ * choice was taken on).  The choice is taken on correctly rounded scores: a token
+ * whose leading k+1 scores are not clearly separated after the fast fp32 gate
+ * product is re-evaluated with fp64 sums.
+ */
+int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
+              const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
+              void* hip_stream);
+
+/*
+ * Expert load + dispatch (Section 4.1: the load of expert e is its token count;
+ * Section 2.2: the scatter that brings tokens to their designated experts).
+ *   counts[e]  = number of assignments a = t*k+j with topk_idx[a] == e
+ *   offsets    = exclusive prefix sum of counts, offsets[E] = T*k
+ *   dst_row[a] = offsets[e] + number of assignments a' < a with the same expert
+ *   src_assign[dst_row[a]] = a
+ *   x_perm[dst_row[a], :] = x[a / k, :]
+ * counts [E], offsets [E+1], dst_row [T*k], src_assign [T*k] int32; x_perm
+ * [T*k,d] in `dtype`.  workspace: at least moe_workspace_bytes() bytes, 16-byte
+ * aligned, contents ignored on entry.  x_perm may be NULL to skip the row copy.
+ */
+int moe_count_and_permute(const moe_shape_t* shape, const void* x, const int32_t* topk_idx,
+                          int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                          int32_t* src_assign, void* x_perm, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Grouped expert FFN (Section 3.2: expert computation dominates the layer).
+ * For every expert e and every row r in [offsets[e], offsets[e+1]):
+ *   h[r,:]      = silu(w1[e] x_perm[r]) * (w3[e] x_perm[r])     silu(z) = z / (1 + exp(-z))
+ *   y_perm[r,:] = w2[e] h[r]
+ * x_perm [T*k,d]; w1, w3 [E,F,d]; w2 [E,d,F]; h [T*k,F] (caller-provided scratch,
+ * holds the activations on return); y_perm [T*k,d]; all in `dtype`; offsets [E+1]
+ * int32 on the device (read by the kernels; no host round trip).
+ */
+int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
+                    const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
+                    void* hip_stream);
+
+/*
+ * Weighted combine (Section 2.2: the gather that collects and reorders expert
+ * outputs):   y[t,:] = sum_{j<k} topk_w[t,j] * y_perm[dst_row[t*k+j], :]
+ * summed in fp32 in ascending j, stored once in `dtype`.  y [T,d].
+ */
+int moe_combine(const moe_shape_t* shape, const void* y_perm, const int32_t* dst_row,
+                const float* topk_w, void* y, void* hip_stream);
+
+/* Static, human-readable text for a status code. */
+const char* moe_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_GFX950_H */
