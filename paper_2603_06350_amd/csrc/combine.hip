@@ -1,0 +1,109 @@
+// moe_combine: y[t,:] = sum_{j<k} topk_w[t,j] * y_perm[dst_row[t*k+j], :]
+// The single-GPU form of the "gather" of Section 2.2 (collect the expert outputs
+// and put them back in token order), fused with the routing-weight scaling of
+// y = sum_k g_k(x) E_k(x).  Written as a gather per output token rather than a
+// scatter-add: every output element is produced by exactly one lane, summed in
+// fp32 in ascending j, so the result is deterministic and needs no atomics and no
+// zero-fill of y.  HBM-bound: reads T*k*d*b, writes T*d*b.
+#include "moe_internal.h"
+
+namespace moe {
+
+// one wave per (token, slab of 64*UNR 16-byte column chunks)
+template <bool BF16, int UNR>
+__global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ y_perm,
+                                                      const int32_t* __restrict__ dst_row,
+                                                      const float* __restrict__ topk_w,
+                                                      uint4* __restrict__ y, int T, int k,
+                                                      int row16, int A) {
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int t = blockIdx.x * (256 / MOE_WAVE) + threadIdx.x / MOE_WAVE;
+  if (t >= T) return;
+  int my_dst = 0;
+  float my_w = 0.f;
+  if (lane < k) {
+    my_dst = dst_row[static_cast<int64_t>(t) * k + lane];
+    my_w = topk_w[static_cast<int64_t>(t) * k + lane];
+  }
+  if (static_cast<unsigned>(my_dst) >= static_cast<unsigned>(A)) my_dst = 0;
+  constexpr int NACC = BF16 ? 8 : 4;
+  const int c_begin = blockIdx.y * (UNR * MOE_WAVE);
+  float acc[UNR][NACC];
+#pragma unroll
+  for (int u = 0; u < UNR; ++u)
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) acc[u][i] = 0.f;
+  for (int j = 0; j < k; ++j) {
+    const int src = __shfl(my_dst, j);
+    const float w = __shfl(my_w, j);
+    const uint4* in = y_perm + static_cast<int64_t>(src) * row16;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int c = c_begin + u * MOE_WAVE + lane;
+      if (c < row16) {
+        const uint4 v = in[c];
+        if (BF16) {
+          acc[u][0] = fmaf(w, bf16lo(v.x), acc[u][0]);
+          acc[u][1] = fmaf(w, bf16hi(v.x), acc[u][1]);
+          acc[u][2] = fmaf(w, bf16lo(v.y), acc[u][2]);
+          acc[u][3] = fmaf(w, bf16hi(v.y), acc[u][3]);
+          acc[u][4] = fmaf(w, bf16lo(v.z), acc[u][4]);
+          acc[u][5] = fmaf(w, bf16hi(v.z), acc[u][5]);
+          acc[u][6] = fmaf(w, bf16lo(v.w), acc[u][6]);
+          acc[u][7] = fmaf(w, bf16hi(v.w), acc[u][7]);
+        } else {
+          acc[u][0] = fmaf(w, __uint_as_float(v.x), acc[u][0]);
+          acc[u][1] = fmaf(w, __uint_as_float(v.y), acc[u][1]);
+          acc[u][2] = fmaf(w, __uint_as_float(v.z), acc[u][2]);
+          acc[u][3] = fmaf(w, __uint_as_float(v.w), acc[u][3]);
+        }
+      }
+    }
+  }
+  uint4* out = y + static_cast<int64_t>(t) * row16;
+#pragma unroll
+  for (int u = 0; u < UNR; ++u) {
+    const int c = c_begin + u * MOE_WAVE + lane;
+    if (c < row16) {
+      uint4 v;
+      if (BF16) {
+        v.x = pack_bf16x2(acc[u][0], acc[u][1]);
+        v.y = pack_bf16x2(acc[u][2], acc[u][3]);
+        v.z = pack_bf16x2(acc[u][4], acc[u][5]);
+        v.w = pack_bf16x2(acc[u][6], acc[u][7]);
+      } else {
+        v.x = __float_as_uint(acc[u][0]);
+        v.y = __float_as_uint(acc[u][1]);
+        v.z = __float_as_uint(acc[u][2]);
+        v.w = __float_as_uint(acc[u][3]);
+      }
+      out[c] = v;
+    }
+  }
+}
+
+}  // namespace moe
+
+extern "C" int moe_combine(const moe_shape_t* shape, const void* y_perm, const int32_t* dst_row,
+                           const float* topk_w, void* y, void* hip_stream) {
+  const int rc = moe::check_shape(shape);
+  if (rc != MOE_OK) return rc;
+  const int T = shape->T;
+  if (T == 0) return MOE_OK;
+  if (!y_perm || !dst_row || !topk_w || !y) return MOE_ERR_INVALID_ARG;
+  if (!moe::aligned16(y_perm) || !moe::aligned16(y)) return MOE_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int row16 =
+      static_cast<int>(static_cast<int64_t>(shape->d) * moe::elem_bytes(shape->dtype) / 16);
+  constexpr int UNR = 4;
+  dim3 grid((T + 3) / 4, (row16 + UNR * MOE_WAVE - 1) / (UNR * MOE_WAVE));
+  if (shape->dtype == MOE_BF16)
+    hipLaunchKernelGGL((moe::combine_kernel<true, UNR>), grid, dim3(256), 0, st,
+                       static_cast<const uint4*>(y_perm), dst_row, topk_w,
+                       static_cast<uint4*>(y), T, shape->k, row16, T * shape->k);
+  else
+    hipLaunchKernelGGL((moe::combine_kernel<false, UNR>), grid, dim3(256), 0, st,
+                       static_cast<const uint4*>(y_perm), dst_row, topk_w,
+                       static_cast<uint4*>(y), T, shape->k, row16, T * shape->k);
+  return moe::launch_status();
+}

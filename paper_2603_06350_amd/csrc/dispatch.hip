@@ -1,0 +1,262 @@
+// moe_count_and_permute: per-expert token counts (the paper's expert load W_l,
+// Sections 3.3 / 4.1), their prefix sum, the stable expert-contiguous permutation
+// of the T*k assignments and the row gather that realises the single-GPU "scatter"
+// of Section 2.2.
+//
+// Three launches on the caller's stream, no host synchronisation:
+//   1. hist_kernel   one thread per token; LDS histogram of the block's
+//                    assignments -> partial[block][expert]              (integer)
+//   2. rank_kernel   same token partition.  Every block sums `partial` to get
+//                    counts, offsets and its own base row per expert, then ranks
+//                    its assignments with a per-(expert, thread) LDS counter table
+//                    and a prefix scan over threads, so the rank of an assignment
+//                    is the number of earlier assignments of the same expert: a
+//                    stable order, independent of scheduling, no atomics on the
+//                    result.
+//   3. gather_kernel one wave per token: reads the token row once (16 B per
+//                    lane, coalesced), writes it to its k destination rows.
+//                    HBM-bound: T*d*b bytes read, T*k*d*b written.
+#include "moe_internal.h"
+
+namespace moe {
+
+template <int NTH>
+__global__ __launch_bounds__(NTH) void hist_kernel(const int32_t* __restrict__ topk_idx, int T,
+                                                   int k, int E,
+                                                   int32_t* __restrict__ partial) {
+  __shared__ int32_t hist[MOE_MAX_E];
+  const int tid = threadIdx.x;
+  for (int e = tid; e < E; e += NTH) hist[e] = 0;
+  __syncthreads();
+  const int t = blockIdx.x * NTH + tid;
+  if (t < T) {
+    const int32_t* row = topk_idx + static_cast<int64_t>(t) * k;
+    for (int j = 0; j < k; ++j) {
+      const int e = row[j];
+      if (static_cast<unsigned>(e) < static_cast<unsigned>(E)) atomicAdd(&hist[e], 1);
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < E; e += NTH) partial[static_cast<int64_t>(blockIdx.x) * E + e] = hist[e];
+}
+
+// Dynamic LDS layout: uint16 cnt[E][NTH] | int32 tot[E] | int32 base[E]
+template <int NTH>
+__global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ topk_idx, int T,
+                                                   int k, int E,
+                                                   const int32_t* __restrict__ partial, int NB,
+                                                   int32_t* __restrict__ counts,
+                                                   int32_t* __restrict__ offsets,
+                                                   int32_t* __restrict__ dst_row,
+                                                   int32_t* __restrict__ src_assign) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint16_t* cnt = reinterpret_cast<uint16_t*>(smem);
+  int32_t* tot = reinterpret_cast<int32_t*>(smem + static_cast<size_t>(E) * NTH * 2);
+  int32_t* base = tot + E;
+  constexpr int NW = NTH / MOE_WAVE;
+  constexpr int PER = NTH / MOE_WAVE;  // table entries of one row held by one lane
+  const int tid = threadIdx.x;
+  const int lane = tid & (MOE_WAVE - 1);
+  const int wave = tid / MOE_WAVE;
+  const int b = blockIdx.x;
+
+  // zero the counter table (16 B per store)
+  {
+    uint4* z = reinterpret_cast<uint4*>(cnt);
+    const int n16 = E * NTH * 2 / 16;
+    for (int i = tid; i < n16; i += NTH) z[i] = make_uint4(0, 0, 0, 0);
+  }
+  // totals per expert and the part that belongs to earlier blocks
+  for (int e = tid; e < E; e += NTH) {
+    int total = 0, before = 0;
+    for (int bb = 0; bb < NB; ++bb) {
+      const int v = partial[static_cast<int64_t>(bb) * E + e];
+      total += v;
+      before += (bb < b) ? v : 0;
+    }
+    tot[e] = total;
+    base[e] = before;
+  }
+  __syncthreads();
+  // exclusive scan of tot over experts by wave 0 (E <= 256: at most 4 per lane)
+  if (wave == 0) {
+    const int per = (E + MOE_WAVE - 1) / MOE_WAVE;
+    const int e0 = lane * per;
+    int local = 0;
+    for (int i = 0; i < per; ++i)
+      if (e0 + i < E) local += tot[e0 + i];
+    int incl = local;
+    for (int off = 1; off < MOE_WAVE; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    int run = incl - local;
+    for (int i = 0; i < per; ++i) {
+      const int e = e0 + i;
+      if (e < E) {
+        const int c = tot[e];
+        if (b == 0) {
+          counts[e] = c;
+          offsets[e] = run;
+        }
+        base[e] += run;
+        run += c;
+      }
+    }
+    if (b == 0 && lane == MOE_WAVE - 1) offsets[E] = incl;
+  }
+  // count this thread's assignments in its private column of the table
+  const int t = b * NTH + tid;
+  const int32_t* row = topk_idx + static_cast<int64_t>(t) * k;
+  if (t < T) {
+    for (int j = 0; j < k; ++j) {
+      const int e = row[j];
+      if (static_cast<unsigned>(e) < static_cast<unsigned>(E)) cnt[e * NTH + tid] += 1;
+    }
+  }
+  __syncthreads();
+  // per expert: exclusive prefix over threads (in place); rows are dealt to waves
+  for (int e = wave; e < E; e += NW) {
+    uint16_t* r = cnt + e * NTH + lane * PER;
+    uint16_t v[PER];
+    int local = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      v[i] = r[i];
+      local += v[i];
+    }
+    int incl = local;
+#pragma unroll
+    for (int off = 1; off < MOE_WAVE; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    int run = incl - local;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      r[i] = static_cast<uint16_t>(run);
+      run += v[i];
+    }
+  }
+  __syncthreads();
+  if (t < T) {
+    for (int j = 0; j < k; ++j) {
+      const int e = row[j];
+      const int a = t * k + j;
+      if (static_cast<unsigned>(e) < static_cast<unsigned>(E)) {
+        const int r = cnt[e * NTH + tid];
+        cnt[e * NTH + tid] = static_cast<uint16_t>(r + 1);
+        const int dst = base[e] + r;
+        dst_row[a] = dst;
+        src_assign[dst] = a;
+      } else {
+        dst_row[a] = 0;  // invalid expert index: value unspecified, stays in bounds
+      }
+    }
+  }
+}
+
+// One wave per token.  row16 = row size in 16-byte units.
+__global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ x,
+                                                     const int32_t* __restrict__ dst_row,
+                                                     uint4* __restrict__ x_perm, int T, int k,
+                                                     int row16, int A) {
+  const int lane = threadIdx.x & (MOE_WAVE - 1);
+  const int t = blockIdx.x * (256 / MOE_WAVE) + threadIdx.x / MOE_WAVE;
+  if (t >= T) return;
+  int my_dst = 0;
+  if (lane < k) my_dst = dst_row[static_cast<int64_t>(t) * k + lane];
+  if (static_cast<unsigned>(my_dst) >= static_cast<unsigned>(A)) my_dst = 0;
+  const uint4* src = x + static_cast<int64_t>(t) * row16;
+  for (int c0 = 0; c0 < row16; c0 += 4 * MOE_WAVE) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + u * MOE_WAVE + lane;
+      if (c < row16) v[u] = src[c];
+    }
+    for (int j = 0; j < k; ++j) {
+      const int dst = __shfl(my_dst, j);
+      uint4* out = x_perm + static_cast<int64_t>(dst) * row16;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + u * MOE_WAVE + lane;
+        if (c < row16) out[c] = v[u];
+      }
+    }
+  }
+}
+
+static int dispatch_threads(int E) { return E <= 128 ? 256 : 128; }
+
+}  // namespace moe
+
+extern "C" int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes) {
+  const int rc = moe::check_shape(shape);
+  if (rc != MOE_OK) return rc;
+  if (!out_bytes) return MOE_ERR_INVALID_ARG;
+  const int nth = moe::dispatch_threads(shape->E);
+  const int64_t nb = (static_cast<int64_t>(shape->T) + nth - 1) / nth;
+  size_t bytes = static_cast<size_t>(nb > 0 ? nb : 1) * shape->E * sizeof(int32_t);
+  *out_bytes = (bytes + 255) & ~static_cast<size_t>(255);
+  return MOE_OK;
+}
+
+extern "C" int moe_count_and_permute(const moe_shape_t* shape, const void* x,
+                                     const int32_t* topk_idx, int32_t* counts, int32_t* offsets,
+                                     int32_t* dst_row, int32_t* src_assign, void* x_perm,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = moe::check_shape(shape);
+  if (rc != MOE_OK) return rc;
+  if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+  size_t need = 0;
+  moe_workspace_bytes(shape, &need);
+  if (!workspace || !moe::aligned16(workspace)) return MOE_ERR_INVALID_ARG;
+  if (workspace_bytes < need) return MOE_ERR_WORKSPACE;
+  const int T = shape->T, k = shape->k, E = shape->E;
+  if (T > 0 && (!topk_idx || !dst_row || !src_assign)) return MOE_ERR_INVALID_ARG;
+  if (T > 0 && x_perm && (!x || !moe::aligned16(x) || !moe::aligned16(x_perm)))
+    return MOE_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int nth = moe::dispatch_threads(E);
+  const int nb = (T + nth - 1) / nth;
+  int32_t* partial = static_cast<int32_t*>(workspace);
+  const size_t lds = static_cast<size_t>(E) * nth * 2 + static_cast<size_t>(E) * 8;
+  // T == 0 still defines counts = 0 and offsets = 0: one block with no tokens does that.
+  const int grid = nb > 0 ? nb : 1;
+  if (nth == 256) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(moe::rank_kernel<256>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              128 * 256 * 2 + 128 * 8) != hipSuccess)
+        return MOE_ERR_HIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(moe::hist_kernel<256>, dim3(grid), dim3(256), 0, st, topk_idx, T, k, E,
+                       partial);
+    hipLaunchKernelGGL(moe::rank_kernel<256>, dim3(grid), dim3(256), lds, st, topk_idx, T, k, E,
+                       partial, grid, counts, offsets, dst_row, src_assign);
+  } else {
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(moe::rank_kernel<128>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              256 * 128 * 2 + 256 * 8) != hipSuccess)
+        return MOE_ERR_HIP;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(moe::hist_kernel<128>, dim3(grid), dim3(128), 0, st, topk_idx, T, k, E,
+                       partial);
+    hipLaunchKernelGGL(moe::rank_kernel<128>, dim3(grid), dim3(128), lds, st, topk_idx, T, k, E,
+                       partial, grid, counts, offsets, dst_row, src_assign);
+  }
+  if (T > 0 && x_perm) {
+    const int row16 = static_cast<int>(static_cast<int64_t>(shape->d) *
+                                       moe::elem_bytes(shape->dtype) / 16);
+    hipLaunchKernelGGL(moe::gather_kernel, dim3((T + 3) / 4), dim3(256), 0, st,
+                       static_cast<const uint4*>(x), dst_row, static_cast<uint4*>(x_perm), T, k,
+                       row16, T * k);
+  }
+  return moe::launch_status();
+}

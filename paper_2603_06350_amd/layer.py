@@ -1,0 +1,62 @@
+"""Device buffers for one MoE layer and the four-call forward.
+
+PyTorch is used for device memory and the stream handle only; the arithmetic is
+in libmoe_gfx950.so.  `MoeBuffers` owns every output and scratch tensor of the
+layer so that repeated forwards allocate nothing.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def to_device(a: np.ndarray, device="cuda"):
+    """Host array from synth_inputs -> device tensor (uint16 bf16 bits become torch.bfloat16)."""
+    if a is None:
+        return None
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> host array (torch.bfloat16 comes back as uint16 bit patterns)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+class MoeBuffers:
+    def __init__(self, T, d, E, k, F, dtype, renorm, device="cuda"):
+        self.shape = B.make_shape(T, d, E, k, F, dtype, renorm)
+        self.T, self.d, self.E, self.k, self.F = T, d, E, k, F
+        tdt = torch.float32 if dtype == B.MOE_F32 else torch.bfloat16
+        A = T * k
+        kw = dict(device=device)
+        self.topk_idx = torch.empty((T, k), dtype=torch.int32, **kw)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, **kw)
+        self.scores = torch.empty((T, E), dtype=torch.float32, **kw)
+        self.counts = torch.empty((E,), dtype=torch.int32, **kw)
+        self.offsets = torch.empty((E + 1,), dtype=torch.int32, **kw)
+        self.dst_row = torch.empty((A,), dtype=torch.int32, **kw)
+        self.src_assign = torch.empty((A,), dtype=torch.int32, **kw)
+        self.x_perm = torch.empty((A, d), dtype=tdt, **kw)
+        self.h = torch.empty((A, F), dtype=tdt, **kw)
+        self.y_perm = torch.empty((A, d), dtype=tdt, **kw)
+        self.y = torch.empty((T, d), dtype=tdt, **kw)
+        self.ws_bytes = B.moe_workspace_bytes(self.shape)
+        self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, **kw)
+
+    def forward(self, x, w_gate, w1, w3, w2, gate_bias=None, stream=None, export_scores=False):
+        """The whole hot path: route -> count+permute -> grouped FFN -> combine."""
+        s = torch.cuda.current_stream() if stream is None else stream
+        B.moe_route(self.shape, x, w_gate, gate_bias, self.topk_idx, self.topk_w,
+                    self.scores if export_scores else None, s)
+        B.moe_count_and_permute(self.shape, x, self.topk_idx, self.counts, self.offsets,
+                                self.dst_row, self.src_assign, self.x_perm, self.workspace,
+                                self.ws_bytes, s)
+        B.moe_grouped_ffn(self.shape, self.x_perm, self.offsets, w1, w3, w2, self.h, self.y_perm, s)
+        B.moe_combine(self.shape, self.y_perm, self.dst_row, self.topk_w, self.y, s)
+        return self.y

@@ -1,0 +1,104 @@
+"""CPU-side checks of the boundary: the shared library loads, exports every symbol that
+include/moe.h declares, and its host-only logic (argument validation, workspace sizing,
+status text) behaves as documented.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_06350_amd import binding as B
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.lib_path()):
+        from paper_2603_06350_amd import build
+        build.build()
+    return B.load()
+
+
+def declared_functions(repo_root):
+    text = open(os.path.join(repo_root, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib, repo_root):
+    names = declared_functions(repo_root)
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_header_has_no_torch_or_cpp_types(repo_root):
+    text = open(os.path.join(repo_root, "include", "moe.h")).read()
+    assert 'extern "C"' in text
+    for banned in ("torch", "at::", "std::", "hipStream_t "):
+        assert banned not in re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+
+
+def test_strerror(lib):
+    assert B.strerror(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert B.strerror(code) not in ("ok", "unknown status")
+    assert B.strerror(-99) == "unknown status"
+
+
+def test_shape_validation_happens_before_any_launch(lib):
+    ok = B.make_shape(64, 128, 8, 2, 256, B.MOE_BF16, 1)
+    assert B.moe_workspace_bytes(ok) >= 8 * 4
+    bad = [
+        B.make_shape(64, 128, 8, 9, 256, B.MOE_BF16, 1),     # k > E
+        B.make_shape(64, 128, 8, 0, 256, B.MOE_BF16, 1),     # k < 1
+        B.make_shape(64, 124, 8, 2, 256, B.MOE_BF16, 1),     # d*2 not a multiple of 16
+        B.make_shape(64, 128, 8, 2, 250, B.MOE_BF16, 1),     # F*2 not a multiple of 16
+        B.make_shape(64, 128, 8, 2, 256, 7, 1),              # dtype
+        B.make_shape(64, 128, 8, 2, 256, B.MOE_BF16, 2),     # renorm
+        B.make_shape(-1, 128, 8, 2, 256, B.MOE_BF16, 1),     # T < 0
+    ]
+    for s in bad:
+        with pytest.raises(B.MoeError) as ei:
+            B.moe_workspace_bytes(s)
+        assert ei.value.code == -1
+    for s in (B.make_shape(64, 128, 300, 2, 256, B.MOE_BF16, 1),      # E > 256
+              B.make_shape(1 << 30, 128, 8, 4, 256, B.MOE_BF16, 1)):  # T*k >= 2^31
+        with pytest.raises(B.MoeError) as ei:
+            B.moe_workspace_bytes(s)
+        assert ei.value.code == -2
+    # null pointers are rejected by every call, on the host
+    for call in (lambda: B.moe_route(ok, None, None, None, None, None),
+                 lambda: B.moe_count_and_permute(ok, None, None, None, None, None, None, None,
+                                                 None, 0),
+                 lambda: B.moe_grouped_ffn(ok, None, None, None, None, None, None, None),
+                 lambda: B.moe_combine(ok, None, None, None, None)):
+        with pytest.raises(B.MoeError) as ei:
+            call()
+        assert ei.value.code == -1
+    # misaligned pointer
+    with pytest.raises(B.MoeError):
+        B.moe_combine(ok, 0x1008, 0x1000, 0x1000, 0x1000)
+    # T = 0 is a no-op for the calls that only touch per-token data
+    empty = B.make_shape(0, 128, 8, 2, 256, B.MOE_BF16, 1)
+    B.moe_route(empty, None, None, None, None, None)
+    B.moe_grouped_ffn(empty, None, None, None, None, None, None, None)
+    B.moe_combine(empty, None, None, None, None)
+
+
+def test_workspace_size_grows_with_tokens(lib):
+    small = B.moe_workspace_bytes(B.make_shape(256, 128, 64, 6, 256, B.MOE_BF16, 0))
+    large = B.moe_workspace_bytes(B.make_shape(8192, 128, 64, 6, 256, B.MOE_BF16, 0))
+    assert large >= 32 * 64 * 4 and small >= 64 * 4 and large > small
+    assert small % 256 == 0 and large % 256 == 0
+
+
+def test_product_package_does_not_import_the_oracle(repo_root):
+    pkg = os.path.join(repo_root, "paper_2603_06350_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                src = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), fn
+    for fn in os.listdir(os.path.join(repo_root, "oracle")):
+        if fn.endswith(".py"):
+            assert "paper_2603_06350_amd" not in open(os.path.join(repo_root, "oracle", fn)).read()

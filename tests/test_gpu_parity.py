@@ -1,0 +1,335 @@
+"""GPU parity: every C-ABI call against the CPU oracle, element by element, on seeded
+inputs.  Each call is first tested alone with oracle-made inputs (so one stage's
+parity does not lean on another's), then the four calls are chained.
+
+Bars: indices, counts, offsets and both permutation maps bit-exact; x_perm bit-exact
+(a copy); routing weights 1e-5 relative; scores 1e-5 of the row's largest magnitude;
+h, y_perm, y within max|gpu - ref| / max|ref| <= 2e-2 (bf16) or 1e-4 (fp32).
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import moe_oracle as orc
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from paper_2603_06350_amd import binding as B  # noqa: E402
+from paper_2603_06350_amd import layer  # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    B.load()
+
+
+def tol_of(dtype):
+    return 1e-4 if dtype == si.F32 else 2e-2
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / (scale if scale > 0 else 1.0))
+
+
+def dev(a):
+    return layer.to_device(a)
+
+
+def host(t):
+    return layer.to_host(t)
+
+
+def shape_of(cfg):
+    return B.make_shape(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+
+
+def tdtype(cfg):
+    return torch.float32 if cfg.dtype == si.F32 else torch.bfloat16
+
+
+# ----------------------------------------------------------------------------- route
+def gpu_route(cfg, x, w_gate, bias):
+    T, E, k = cfg.T, cfg.E, cfg.k
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((T, k), dtype=torch.float32, device="cuda")
+    sc = torch.zeros((T, E), dtype=torch.float32, device="cuda")
+    B.moe_route(shape_of(cfg), dev(x), dev(w_gate), dev(bias), idx, w, sc)
+    torch.cuda.synchronize()
+    return host(idx), host(w), host(sc)
+
+
+def check_route(cfg, x, w_gate, bias):
+    idx, w, sc = gpu_route(cfg, x, w_gate, bias)
+    ridx, rw, rsc = orc.route(x, w_gate, cfg.k, cfg.renorm, bias)
+    row_scale = np.maximum(np.abs(rsc).max(axis=1, keepdims=True), 1e-30)
+    assert (np.abs(sc - rsc) / row_scale).max() <= 1e-5
+    bad = np.nonzero((idx != ridx).any(axis=1))[0]
+    assert bad.size == 0, f"{cfg.name}: top-k differs on rows {bad[:8]} gpu {idx[bad[:3]]} ref {ridx[bad[:3]]}"
+    assert np.abs(w - rw).max() <= 1e-5 * max(1e-30, np.abs(rw).max())
+    assert np.all(np.abs(w - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+    return idx, w
+
+
+ROUTE_CASES = [
+    dict(T=300, d=256, E=8, k=2, renorm=1),
+    dict(T=1000, d=512, E=64, k=6, renorm=0),
+    dict(T=77, d=1024, E=128, k=8, renorm=1),
+    dict(T=130, d=264, E=200, k=5, renorm=1),     # d not a multiple of 32, E > 128
+    dict(T=50, d=64, E=16, k=1, renorm=1),        # k = 1 (Llama-4-Scout style)
+    dict(T=33, d=128, E=4, k=4, renorm=0),        # k = E
+    dict(T=1, d=4096, E=8, k=2, renorm=1),        # one token
+    dict(T=40, d=96, E=24, k=3, renorm=1, dtype=si.F32),
+]
+
+
+@pytest.mark.parametrize("case", ROUTE_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}".format(**c))
+def test_route_matches_oracle(case):
+    cfg = si.small_config(F=64, **case)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    check_route(cfg, L["x"], L["w_gate"], None)
+
+
+def test_route_exact_ties_go_to_lowest_index():
+    cfg = si.small_config(T=200, d=256, E=16, k=4, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    wg = L["w_gate"].copy()
+    wg[9] = wg[2]
+    wg[13] = wg[2]
+    check_route(cfg, L["x"], wg, None)
+    idx, w = check_route(cfg, np.zeros_like(L["x"]), wg, None)
+    assert np.array_equal(idx, np.tile(np.arange(4, dtype=np.int32), (cfg.T, 1)))
+
+
+def test_route_with_bias_and_forced_expert():
+    cfg = si.small_config(T=150, d=256, E=64, k=6, F=64, renorm=0)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    bias = np.linspace(-2, 2, 64).astype(np.float32)
+    check_route(cfg, L["x"], L["w_gate"], bias)
+    bias[5] = 1e9
+    bias[60:] = -1e9
+    idx, _ = check_route(cfg, L["x"], L["w_gate"], bias)
+    assert np.all(idx[:, 0] == 5) and idx.max() < 60
+
+
+def test_route_near_ties_are_decided_like_the_oracle():
+    # experts 1 and 3 share their weights and differ by a 1e-6 bias: their scores are a few
+    # fp32 ulps apart, which a differently ordered fp32 sum cannot resolve but the exact pass must
+    cfg = si.small_config(T=256, d=512, E=8, k=2, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    wg = L["w_gate"].copy()
+    wg[3] = wg[1]
+    bias = np.zeros(8, dtype=np.float32)
+    bias[3] = 1e-6
+    _, _, rsc = orc.route(L["x"], wg, 2, 1, bias)
+    m = orc.topk_margin(rsc, 2)
+    assert ((m < 1e-4) & (m > 0)).sum() > 5     # near-ties (not exact ties) at the k-th place
+    check_route(cfg, L["x"], wg, bias)
+    bias[3] = -1e-6
+    check_route(cfg, L["x"], wg, bias)
+
+
+# ----------------------------------------------------------------------------- count + permute
+def gpu_dispatch(cfg, x, idx):
+    T, E, k, d = cfg.T, cfg.E, cfg.k, cfg.d
+    sh = shape_of(cfg)
+    A = T * k
+    counts = torch.full((E,), -7, dtype=torch.int32, device="cuda")
+    offsets = torch.full((E + 1,), -7, dtype=torch.int32, device="cuda")
+    dst = torch.full((max(A, 1),), -7, dtype=torch.int32, device="cuda")
+    src = torch.full((max(A, 1),), -7, dtype=torch.int32, device="cuda")
+    xp = torch.zeros((max(A, 1), d), dtype=tdtype(cfg), device="cuda")
+    nb = B.moe_workspace_bytes(sh)
+    ws = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda")   # garbage on entry
+    B.moe_count_and_permute(sh, dev(x), dev(idx), counts, offsets, dst, src, xp, ws, nb)
+    torch.cuda.synchronize()
+    return host(counts), host(offsets), host(dst)[:A], host(src)[:A], host(xp)[:A]
+
+
+def check_dispatch(cfg, x, idx):
+    counts, offsets, dst, src, xp = gpu_dispatch(cfg, x, idx)
+    rc, ro = orc.expert_load(idx, cfg.E)
+    rd, rs = orc.permutation(idx, cfg.E)
+    assert np.array_equal(counts, rc)
+    assert np.array_equal(offsets, ro)
+    assert np.array_equal(dst, rd)
+    assert np.array_equal(src, rs)
+    assert np.array_equal(xp, orc.permute_rows(x, rd, cfg.k))
+    assert counts.sum() == cfg.T * cfg.k
+
+
+DISPATCH_CASES = [
+    dict(T=300, d=256, E=8, k=2),
+    dict(T=1000, d=128, E=64, k=6),       # several blocks of 256 tokens, ragged tail
+    dict(T=513, d=64, E=128, k=8),
+    dict(T=700, d=72, E=256, k=3),        # 128-thread variant, row not a multiple of 64 B
+    dict(T=1, d=4096, E=8, k=2),
+    dict(T=40, d=96, E=24, k=3, dtype=si.F32),
+]
+
+
+@pytest.mark.parametrize("case", DISPATCH_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}".format(**c))
+def test_count_and_permute_matches_oracle(case):
+    cfg = si.small_config(F=64, **case)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    idx, _, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm)
+    check_dispatch(cfg, L["x"], idx)
+
+
+def test_count_and_permute_degenerate_loads():
+    cfg = si.small_config(T=600, d=64, E=16, k=2, F=64)
+    L = si.make_layer(cfg, parts=("x",))
+    idx = np.zeros((cfg.T, 2), dtype=np.int32)
+    idx[:, 0], idx[:, 1] = 7, 3                       # two experts take everything, 14 are empty
+    check_dispatch(cfg, L["x"], idx)
+    rng = np.random.default_rng(0)
+    idx = rng.integers(0, 16, size=(cfg.T, 2)).astype(np.int32)   # a token may repeat an expert
+    check_dispatch(cfg, L["x"], idx)
+    cfg1 = si.small_config(T=600, d=64, E=16, k=1, F=64)
+    check_dispatch(cfg1, L["x"], np.full((cfg.T, 1), 15, dtype=np.int32))
+
+
+def test_count_and_permute_no_tokens():
+    cfg = si.small_config(T=0, d=64, E=8, k=2, F=64)
+    sh = shape_of(cfg)
+    counts = torch.full((8,), -7, dtype=torch.int32, device="cuda")
+    offsets = torch.full((9,), -7, dtype=torch.int32, device="cuda")
+    nb = B.moe_workspace_bytes(sh)
+    ws = torch.empty((nb,), dtype=torch.uint8, device="cuda")
+    B.moe_count_and_permute(sh, None, None, counts, offsets, None, None, None, ws, nb)
+    torch.cuda.synchronize()
+    assert host(counts).tolist() == [0] * 8 and host(offsets).tolist() == [0] * 9
+
+
+# ----------------------------------------------------------------------------- grouped FFN
+def gpu_ffn(cfg, x_perm, offsets, w1, w3, w2):
+    A = cfg.T * cfg.k
+    h = torch.zeros((A, cfg.F), dtype=tdtype(cfg), device="cuda")
+    yp = torch.zeros((A, cfg.d), dtype=tdtype(cfg), device="cuda")
+    B.moe_grouped_ffn(shape_of(cfg), dev(x_perm), dev(offsets), dev(w1), dev(w3), dev(w2), h, yp)
+    torch.cuda.synchronize()
+    return orc.to_f64(host(h)), orc.to_f64(host(yp))
+
+
+def check_ffn(cfg, L, idx):
+    _, offsets = orc.expert_load(idx, cfg.E)
+    dst, _ = orc.permutation(idx, cfg.E)
+    x_perm = orc.permute_rows(L["x"], dst, cfg.k)
+    ry, rh = orc.grouped_ffn(x_perm, offsets, L["w1"], L["w3"], L["w2"], return_h=True)
+    h, yp = gpu_ffn(cfg, x_perm, offsets, L["w1"], L["w3"], L["w2"])
+    tol = tol_of(cfg.dtype)
+    assert rel_err(h, rh) <= tol, f"h: {rel_err(h, rh):.3e}"
+    assert rel_err(yp, ry) <= tol, f"y_perm: {rel_err(yp, ry):.3e}"
+    # per-row check too: a wrong row hiding behind a large global scale would show here
+    row_scale = np.abs(ry).max(axis=1) + 1e-30
+    assert (np.abs(yp - ry).max(axis=1) / row_scale).max() <= 4 * tol
+    return x_perm, offsets, dst
+
+
+FFN_CASES = [
+    dict(T=300, d=256, E=8, k=2, F=384),          # MFMA path, 128-row tiles, ragged
+    dict(T=1500, d=128, E=2, k=1, F=256),         # MFMA path, 256-row tiles (>= 512 rows/expert)
+    dict(T=900, d=192, E=3, k=2, F=320),          # 256-row tiles, N tails (320 = 2.5 x 128, 192 < 256)
+    dict(T=64, d=512, E=64, k=6, F=128),          # many small / empty experts
+    dict(T=100, d=200, E=4, k=2, F=104),          # bf16 generic path (d, F not multiples of 64)
+    dict(T=64, d=128, E=8, k=2, F=256, dtype=si.F32, x_std=0.02, w_std=0.02),
+    dict(T=45, d=36, E=5, k=2, F=52, dtype=si.F32),
+]
+
+
+@pytest.mark.parametrize("case", FFN_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}_F{F}".format(**c))
+def test_grouped_ffn_matches_oracle(case):
+    cfg = si.small_config(**case)
+    L = si.make_layer(cfg)
+    idx, _, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm)
+    check_ffn(cfg, L, idx)
+
+
+def test_grouped_ffn_skewed_and_empty_experts():
+    cfg = si.small_config(T=700, d=128, E=8, k=2, F=256)
+    L = si.make_layer(cfg)
+    idx = np.zeros((cfg.T, 2), dtype=np.int32)
+    idx[:, 0] = 2                                     # 700 rows: 256-row tiles with a tail
+    idx[:, 1] = np.where(np.arange(cfg.T) < 5, 6, 4)  # 5 rows and 695 rows; 5 experts empty
+    check_ffn(cfg, L, idx)
+
+
+def test_identity_experts_reproduce_the_input_on_gpu():
+    # closed form: W1 rows = c*e0, W3 = [I;0], W2 = [I/silu(c), 0]  =>  E(x) = x when x[:,0] = 1
+    T, d, E, k, F = 200, 128, 4, 2, 192
+    cfg = si.small_config(T=T, d=d, E=E, k=k, F=F, dtype=si.F32)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    x = L["x"].copy()
+    x[:, 0] = 1.0
+    c = 1.5
+    s0 = c / (1.0 + np.exp(-c))
+    w1 = np.zeros((E, F, d), np.float32); w1[:, :, 0] = c
+    w3 = np.zeros((E, F, d), np.float32); w3[:, :d, :d] = np.eye(d)
+    w2 = np.zeros((E, d, F), np.float32); w2[:, :d, :d] = np.eye(d) / s0
+    buf = layer.MoeBuffers(T, d, E, k, F, cfg.dtype, 1)
+    buf.forward(dev(x), dev(L["w_gate"]), dev(w1), dev(w3), dev(w2))
+    torch.cuda.synchronize()
+    assert rel_err(host(buf.y), x) <= 1e-5
+
+
+# ----------------------------------------------------------------------------- combine
+@pytest.mark.parametrize("case", [dict(T=300, d=256, E=8, k=2), dict(T=257, d=1032, E=64, k=6),
+                                  dict(T=31, d=4096, E=128, k=8),
+                                  dict(T=40, d=100, E=6, k=3, dtype=si.F32)],
+                         ids=lambda c: "T{T}_d{d}_k{k}".format(**c))
+def test_combine_matches_oracle(case):
+    cfg = si.small_config(F=64, **case)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    idx, w, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm)
+    dst, _ = orc.permutation(idx, cfg.E)
+    # any rows will do as "expert outputs": draw them with the generator
+    yp = si.make_layer(si.small_config(T=cfg.A, d=cfg.d, E=1, k=1, F=8, dtype=cfg.dtype, seed=99),
+                       parts=("x",))["x"]
+    y = torch.zeros((cfg.T, cfg.d), dtype=tdtype(cfg), device="cuda")
+    B.moe_combine(shape_of(cfg), dev(yp), dev(dst), dev(w), y)
+    torch.cuda.synchronize()
+    ref = orc.combine(yp, dst, w)
+    assert rel_err(orc.to_f64(host(y)), ref) <= (1e-6 if cfg.dtype == si.F32 else 4e-3)
+
+
+# ----------------------------------------------------------------------------- whole layer
+LAYER_CASES = [
+    si.CONFIGS["tiny"],
+    si.small_config("bf16_small", T=300, d=256, E=8, k=2, F=384),
+    si.small_config("bf16_fine", T=500, d=256, E=64, k=6, F=128, renorm=0),
+    si.small_config("bf16_big_tiles", T=1400, d=128, E=2, k=2, F=256),
+    si.small_config("bf16_decode_like", T=32, d=512, E=128, k=8, F=192),
+    si.small_config("bf16_skew", T=600, d=256, E=64, k=6, F=128, renorm=0, zipf_alpha=1.2,
+                    zipf_scale=0.9, empty_tail=4),
+]
+
+
+@pytest.mark.parametrize("cfg", LAYER_CASES, ids=lambda c: c.name)
+def test_layer_end_to_end(cfg):
+    L = si.make_layer(cfg)
+    ref = orc.moe_layer(L["x"], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm,
+                        L["gate_bias"])
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    buf.forward(*args, gate_bias=dev(L["gate_bias"]), export_scores=True)
+    torch.cuda.synchronize()
+    first = {n: host(getattr(buf, n)).copy() for n in
+             ("topk_idx", "topk_w", "counts", "offsets", "dst_row", "src_assign", "x_perm", "h",
+              "y_perm", "y")}
+    for n in ("topk_idx", "counts", "offsets", "dst_row", "src_assign", "x_perm"):
+        assert np.array_equal(first[n], ref[n]), n
+    assert np.all(np.abs(first["topk_w"] - ref["topk_w"]) <= 1e-5 * ref["topk_w"] + 1e-9)
+    tol = tol_of(cfg.dtype)
+    for n in ("h", "y_perm", "y"):
+        e = rel_err(orc.to_f64(first[n]), ref[n])
+        assert e <= tol, f"{n}: {e:.3e}"
+    assert first["counts"].sum() == cfg.A
+    # determinism: a second run gives the same bits everywhere
+    buf.forward(*args, gate_bias=dev(L["gate_bias"]), export_scores=True)
+    torch.cuda.synchronize()
+    for n, v in first.items():
+        assert np.array_equal(host(getattr(buf, n)), v), f"{n} differs between two runs"
