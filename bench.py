@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""MoE-layer forward benchmark on one MI355X.
+
+A step is one pass of the whole hot path (moe_route -> moe_count_and_permute ->
+moe_grouped_ffn -> moe_combine) over one seeded synthetic batch that is already
+resident in HBM.  Prints ONE JSON line: whole-layer tokens/s, per-call times, the
+roofline of the dominant kernel (the gated up-projection GEMM of the grouped FFN)
+and the CPU oracle timed on the host cores on a bounded sample of the same batch.
+
+usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mixtral]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+CPU_SAMPLE_TOKENS = {"mixtral": 2048, "finegrained": 2048, "skew": 2048, "decode": 32, "tiny": 64}
+
+
+def algorithmic_work(cfg):
+    """Algorithmic bytes / flops of one launch of each call (per-unit figures x units)."""
+    T, d, E, k, F, b = cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.itemsize
+    A = T * k
+    return {
+        "route_bytes": T * d * b + E * d * b + 8 * A,
+        "permute_bytes": T * d * b + A * d * b + 4 * A + 8 * A + 8 * E,
+        "ffn_up_flops": 4 * d * F * A,        # two d x F products per routed row
+        "ffn_down_flops": 2 * d * F * A,
+        "combine_bytes": A * d * b + T * d * b + 8 * A,
+    }
+
+
+def cpu_baseline(cfg, L, n_tokens):
+    """The oracle, as it stands, on the first n_tokens tokens of the batch (all experts' weights)."""
+    from oracle import moe_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    t0 = time.perf_counter()
+    orc.moe_layer(L["x"][:n_tokens], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm,
+                  L["gate_bias"])
+    dt = time.perf_counter() - t0
+    return {"value": n_tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {n_tokens} of {cfg.T} tokens through the full layer (all {cfg.E} "
+                      f"experts' weights, fp64), {dt:.1f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mixtral")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this build has no sharded path (one process, one "
+              "MI355X); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as si
+    from paper_2603_06350_amd import binding as B
+    from paper_2603_06350_amd import layer
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.load()
+    cfg = si.CONFIGS[args.workload]
+    L = si.make_layer(cfg)
+    x, wg, w1, w3, w2 = (layer.to_device(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2"))
+    bias = layer.to_device(L["gate_bias"])
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    st = torch.cuda.current_stream()
+    sh = buf.shape
+
+    def step():
+        B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
+        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
+                                buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
+        B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+        B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # Per-kernel durations with HIP events on the launch stream (torch events record on the
+    # current stream, which is the stream every call above is given).
+    names = ["route", "count_and_permute", "ffn_up", "ffn_down", "combine"]
+    n_ev = min(args.steps, 50)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(n_ev)]
+    for it in range(n_ev):
+        e = evs[it]
+        e[0].record(st)
+        B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
+        e[1].record(st)
+        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
+                                buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
+        e[2].record(st)
+        B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 1, st)
+        e[3].record(st)
+        B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 2, st)
+        e[4].record(st)
+        B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
+        e[5].record(st)
+    torch.cuda.synchronize()
+    per_call_ms = {n: sum(evs[it][i].elapsed_time(evs[it][i + 1]) for it in range(n_ev)) / n_ev
+                   for i, n in enumerate(names)}
+
+    work = algorithmic_work(cfg)
+    up_s = per_call_ms["ffn_up"] * 1e-3
+    achieved = work["ffn_up_flops"] / up_s / 1e12
+    roofline = {"bound": "mfma", "kernel": "ffn_mfma_kernel<gated> (moe_grouped_ffn part 1)",
+                "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                "flops_per_launch": work["ffn_up_flops"], "avg_launch_ms": per_call_ms["ffn_up"]}
+    others = {
+        "ffn_down_tflops": work["ffn_down_flops"] / (per_call_ms["ffn_down"] * 1e-3) / 1e12,
+        "ffn_total_frac_of_mfma_peak": (work["ffn_up_flops"] + work["ffn_down_flops"]) /
+        ((per_call_ms["ffn_up"] + per_call_ms["ffn_down"]) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "route_gbs": work["route_bytes"] / (per_call_ms["route"] * 1e-3) / 1e9,
+        "count_and_permute_gbs": work["permute_bytes"] / (per_call_ms["count_and_permute"] * 1e-3) / 1e9,
+        "combine_gbs": work["combine_bytes"] / (per_call_ms["combine"] * 1e-3) / 1e9,
+        "hbm_peak_gbs": PEAK_HBM_GBS,
+        "note": "HBM-bound calls re-use the same buffers every step (cache-warm); event "
+                "timings include launch gaps",
+    }
+    out = {
+        "metric": "MoE-layer tokens/sec (Mixtral shape)" if cfg.name == "mixtral"
+        else f"MoE-layer tokens/sec ({cfg.name})",
+        "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == si.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
+                               f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward"},
+        "per_call_ms": per_call_ms, "roofline": roofline, "other_calls": others,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, L, CPU_SAMPLE_TOKENS.get(cfg.name, min(cfg.T, 256)))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -109,6 +109,17 @@ int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t*
                     void* hip_stream);
 
 /*
+ * One half of moe_grouped_ffn (same operation, Section 3.2; same arguments and
+ * rules).  part 1: h = silu(W1 x_perm) * (W3 x_perm); part 2: y_perm = W2 h (reads
+ * the h that part 1 left).  moe_grouped_ffn is part 1 followed by part 2; the
+ * split lets a caller time the two GEMMs apart or put other work between them.
+ * Any other `part` is MOE_ERR_INVALID_ARG.
+ */
+int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
+                         const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
+                         int part, void* hip_stream);
+
+/*
  * Weighted combine (Section 2.2: the gather that collects and reorders expert
  * outputs):   y[t,:] = sum_{j<k} topk_w[t,j] * y_perm[dst_row[t*k+j], :]
  * summed in fp32 in ascending j, stored once in `dtype`.  y [T,d].

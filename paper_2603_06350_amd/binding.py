@@ -1,4 +1,4 @@
-"""ctypes binding of libmoe_gfx950.so: the same five calls as include/moe.h.
+"""ctypes binding of libmoe_gfx950.so: the same calls as include/moe.h.
 
 Argument marshalling only: tensors are passed as device pointers, every step of
 the layer runs in the library's HIP kernels.  There is no CPU fallback; loading
@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_gfx
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",
-           "moe_combine", "moe_strerror")
+           "moe_grouped_ffn_part", "moe_combine", "moe_strerror")
 
 
 class MoeShape(ctypes.Structure):
@@ -50,6 +50,7 @@ def load():
     lib.moe_count_and_permute.argtypes = [shp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp,
                                           ctypes.c_size_t, vp]
     lib.moe_grouped_ffn.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, vp]
+    lib.moe_grouped_ffn_part.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.moe_combine.argtypes = [shp, vp, i32p, f32p, vp, vp]
     lib.moe_strerror.argtypes = [ctypes.c_int]
     lib.moe_strerror.restype = ctypes.c_char_p
@@ -114,6 +115,13 @@ def moe_grouped_ffn(shape, x_perm, offsets, w1, w3, w2, h, y_perm, stream=None):
     _check("moe_grouped_ffn",
            load().moe_grouped_ffn(ctypes.byref(shape), _ptr(x_perm), _ptr(offsets), _ptr(w1),
                                   _ptr(w3), _ptr(w2), _ptr(h), _ptr(y_perm), _stream(stream)))
+
+
+def moe_grouped_ffn_part(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, stream=None):
+    _check("moe_grouped_ffn_part",
+           load().moe_grouped_ffn_part(ctypes.byref(shape), _ptr(x_perm), _ptr(offsets), _ptr(w1),
+                                       _ptr(w3), _ptr(w2), _ptr(h), _ptr(y_perm), int(part),
+                                       _stream(stream)))
 
 
 def moe_combine(shape, y_perm, dst_row, topk_w, y, stream=None):

@@ -399,9 +399,10 @@ static int launch_generic(const GemmArgs& a, int64_t A, hipStream_t st) {
 
 }  // namespace moe
 
-extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
-                               const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
-                               void* hip_stream) {
+// parts: bit 0 = gated up-projection (h), bit 1 = down-projection (y_perm)
+static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
+                            const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
+                            int parts, void* hip_stream) {
   using namespace moe;
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
@@ -415,22 +416,47 @@ extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, con
   const int d = shape->d, F = shape->F, E = shape->E;
   GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A)};
   GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A)};
+  const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
     g2.n_tiles = (d + 255) / 256;
     const bool big = A / E >= 512;
-    rc = big ? launch_mfma<256, true, 4, 2>(g1, A, st) : launch_mfma<128, true, 2, 4>(g1, A, st);
-    if (rc != MOE_OK) return rc;
-    return big ? launch_mfma<256, false, 4, 2>(g2, A, st) : launch_mfma<128, false, 2, 4>(g2, A, st);
+    if (up) {
+      rc = big ? launch_mfma<256, true, 4, 2>(g1, A, st) : launch_mfma<128, true, 2, 4>(g1, A, st);
+      if (rc != MOE_OK) return rc;
+    }
+    if (down)
+      rc = big ? launch_mfma<256, false, 4, 2>(g2, A, st) : launch_mfma<128, false, 2, 4>(g2, A, st);
+    return rc;
   }
   g1.n_tiles = (F + 63) / 64;
   g2.n_tiles = (d + 63) / 64;
   if (shape->dtype == MOE_BF16) {
-    rc = launch_generic<bf16_t, true>(g1, A, st);
-    if (rc != MOE_OK) return rc;
-    return launch_generic<bf16_t, false>(g2, A, st);
+    if (up) {
+      rc = launch_generic<bf16_t, true>(g1, A, st);
+      if (rc != MOE_OK) return rc;
+    }
+    if (down) rc = launch_generic<bf16_t, false>(g2, A, st);
+    return rc;
   }
-  rc = launch_generic<float, true>(g1, A, st);
-  if (rc != MOE_OK) return rc;
-  return launch_generic<float, false>(g2, A, st);
+  if (up) {
+    rc = launch_generic<float, true>(g1, A, st);
+    if (rc != MOE_OK) return rc;
+  }
+  if (down) rc = launch_generic<float, false>(g2, A, st);
+  return rc;
+}
+
+extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
+                               const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
+                               void* hip_stream) {
+  return grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
+}
+
+extern "C" int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm,
+                                    const int32_t* offsets, const void* w1, const void* w3,
+                                    const void* w2, void* h, void* y_perm, int part,
+                                    void* hip_stream) {
+  if (part != 1 && part != 2) return MOE_ERR_INVALID_ARG;
+  return grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, hip_stream);
 }
