@@ -94,6 +94,14 @@ def main():
         B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
         B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
 
+    # One plain copy kernel of known size (1 GiB read + 1 GiB written) so that a profiler's
+    # HBM byte counters can be scaled against a known quantity.  Outside the timed region.
+    calib_src = torch.ones((512 << 20,), dtype=torch.bfloat16, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    torch.mul(calib_src, 1, out=calib_dst)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
