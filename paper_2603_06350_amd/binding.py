@@ -12,7 +12,9 @@ import os
 MOE_F32 = 0
 MOE_BF16 = 1
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_gfx950.so")
+# MOE_GFX950_LIB points the binding at another build of the same library (same C ABI).
+_LIB_PATH = os.environ.get("MOE_GFX950_LIB") or os.path.join(
+    os.path.dirname(os.path.abspath(__file__)), "libmoe_gfx950.so")
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",

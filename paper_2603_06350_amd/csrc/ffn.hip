@@ -2,34 +2,43 @@
 // For every expert e and row r of its segment [offsets[e], offsets[e+1]):
 //   h[r] = silu(W1_e x_perm[r]) * (W3_e x_perm[r]),   y_perm[r] = W2_e h[r].
 //
-// Two launches: a gated GEMM (W1 and W3 tiles side by side, SwiGLU applied to the
-// fp32 accumulators, h stored once) and a plain GEMM for W2.  Both are ragged
-// grouped GEMMs: the tile list is derived on the device from `offsets`, so the host
-// never learns the expert loads.
+// Two GEMMs: a gated one (W1 and W3 tiles side by side, SwiGLU applied to the fp32
+// accumulators, h stored once) and a plain one for W2.  Both are ragged grouped
+// GEMMs: the tile list is derived on the device from `offsets`, so the host never
+// learns the expert loads.  Each GEMM is two launches over disjoint tile lists:
+//   main   block tile BM x 256 weight rows (BM = 256 or 128): every full tile of an
+//          expert's segment, and its remainder if that has more than 64 rows;
+//   small  block tile 64 x 256: remainders of at most 64 rows (the tail of a large
+//          expert, or all of a small one: decode-shaped layers live here).
+// A small tile has little arithmetic per weight byte, so it is paced by memory
+// latency: it runs a four-stage LDS ring with three stages of loads in flight.
 //
-// bf16 kernel (gfx950): 512 threads = 8 waves (two per SIMD, so one wave's LDS
-// waits hide behind the other's MFMAs); block tile BM rows x 256 weight rows,
-// K step 64.  Both operands are K-contiguous in memory, so a tile
-// row is 128 B = eight 16-byte chunks.  Tiles go global -> LDS with the direct
-// 16-byte-per-lane loads (no register staging), double buffered; a wave
+// bf16 kernels (gfx950): 512 threads = 8 waves, two per SIMD.  K step 64: both
+// operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
+// global -> LDS with the direct 16-byte-per-lane loads (no register staging); a wave
 // instruction fills 8 rows, and the chunk a lane fetches is XOR-swizzled by row so
-// that the later 16-byte LDS reads of a 32-row MFMA operand spread over all banks.
-// The weight fragment is fed as the MFMA "A" operand and the activation fragment
-// as "B": each lane then owns 4 consecutive output columns of one output row and
-// stores them as one 8-byte word.  v_mfma_f32_32x32x16_bf16, fp32 accumulators.
+// that the 16-byte LDS reads of a 32-row MFMA operand are bank-conflict free.  The
+// weight fragment is the MFMA "A" operand and the activation fragment "B": a lane then
+// owns 4 consecutive output columns of one output row and stores them as one 8-byte
+// word.  v_mfma_f32_32x32x16_bf16, fp32 accumulators.
 //
 // Work-group ids are remapped so that each XCD (ids are dealt round-robin to the 8
 // XCDs) walks a contiguous range of the tile list with the m-tiles of one weight
 // panel adjacent: CUs that share an L2 share weight tiles.
 //
-// Generic kernel (fp32, or bf16 shapes whose d or F is not a multiple of 64): a
-// plain LDS-tiled FMA GEMM with fp32 accumulation.
+// Generic kernel (fp32, or bf16 shapes whose d or F is not a multiple of 64): a plain
+// LDS-tiled FMA GEMM with fp32 accumulation.
+#include <type_traits>
+
 #include "moe_internal.h"
 
 namespace moe {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+
+enum TileMode { TILES_ALL = 0, TILES_MAIN = 1, TILES_SMALL = 2 };
+constexpr int SMALL_ROWS = 64;  // remainders up to this many rows go to the small-tile kernel
 
 struct GemmArgs {
   const void* a;    // activations [rows, K]
@@ -40,18 +49,23 @@ struct GemmArgs {
   int E, K, N;
   int n_tiles;      // tiles along N
   int rows;         // T*k; row ranges read from `offsets` are clamped to it
+  int mode;         // TileMode
+  int bm_main;      // rows of a main tile (also the unit remainders are taken against)
 };
 
 struct TileCoord {
   int e, m_begin, m_end, n_tile;
 };
 
-// Maps a work-group to (expert, row range, n-tile).  Every wave computes this on
-// its own from the device-resident offsets; returns false if the group has no tile.
-// Tile order: expert-major, then n-tile, then m-tile (m fastest), cut into 8
-// contiguous ranges, one per XCD.
-__device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets, int E, int BM,
-                                            int n_tiles, int rows, TileCoord& tc) {
+// Maps a work-group to (expert, row range, n-tile).  Every wave computes this on its
+// own from the device-resident offsets; returns false if the group has no tile.
+// An expert with c rows has c / bm_main full tiles and a remainder rem = c % bm_main;
+// TILES_ALL lists the full tiles and the remainder, TILES_MAIN drops remainders of at
+// most SMALL_ROWS rows, TILES_SMALL lists only those.  Tile order: expert-major, then
+// n-tile, then m-tile (m fastest), cut into 8 contiguous ranges, one per XCD.
+__device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
+  const int32_t* __restrict__ offsets = p.offsets;
+  const int E = p.E, n_tiles = p.n_tiles, bm = p.bm_main, mode = p.mode;
   const int lane = lane_id();
   const int per = (E + MOE_WAVE - 1) / MOE_WAVE;  // <= 4
   const int e0 = lane * per;
@@ -60,11 +74,16 @@ __device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets,
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int e = e0 + i;
-    int c = 0;
-    if (i < per && e < E) c = (offsets[e + 1] - offsets[e] + BM - 1) / BM;
-    c = max(c, 0);
-    mt[i] = c;
-    local += c;
+    int t = 0;
+    if (i < per && e < E) {
+      const int c = max(offsets[e + 1] - offsets[e], 0);
+      const int full = c / bm, rem = c % bm;
+      if (mode == TILES_ALL) t = full + (rem > 0 ? 1 : 0);
+      else if (mode == TILES_MAIN) t = full + (rem > SMALL_ROWS ? 1 : 0);
+      else t = (rem > 0 && rem <= SMALL_ROWS) ? 1 : 0;
+    }
+    mt[i] = t;
+    local += t;
   }
   int incl = local;
 #pragma unroll
@@ -72,6 +91,7 @@ __device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets,
     const int up = __shfl_up(incl, off);
     if (lane >= off) incl += up;
   }
+  // readfirstlane: the results are wave-uniform; tell the compiler so they live in SGPRs
   const int total = __builtin_amdgcn_readfirstlane(__shfl(incl, MOE_WAVE - 1)) * n_tiles;
   const int per_xcd = (total + 7) / 8;
   const int xcd = blockIdx.x & 7;
@@ -93,15 +113,21 @@ __device__ __forceinline__ bool decode_tile(const int32_t* __restrict__ offsets,
   const unsigned long long who = __ballot(found_e >= 0);
   if (who == 0ull) return false;  // inconsistent offsets: no tile
   const int src = __ffsll(static_cast<long long>(who)) - 1;
-  // readfirstlane: the results are wave-uniform; tell the compiler so they live in SGPRs
   const int e = __builtin_amdgcn_readfirstlane(__shfl(found_e, src));
   const int loc = __builtin_amdgcn_readfirstlane(__shfl(found_local, src));
   const int m_tiles = __builtin_amdgcn_readfirstlane(__shfl(found_mt, src));
   const int m_idx = loc % m_tiles;
+  const int seg_begin = max(offsets[e], 0);
+  const int seg_end = min(offsets[e + 1], p.rows);
   tc.e = e;
   tc.n_tile = loc / m_tiles;
-  tc.m_begin = max(offsets[e], 0) + m_idx * BM;
-  tc.m_end = min(offsets[e + 1], rows);
+  if (mode == TILES_SMALL) {
+    tc.m_begin = seg_begin + ((seg_end - seg_begin) / bm) * bm;
+    tc.m_end = seg_end;
+  } else {
+    tc.m_begin = seg_begin + m_idx * bm;
+    tc.m_end = min(seg_end, tc.m_begin + bm);
+  }
   return tc.m_begin < tc.m_end;
 }
 
@@ -112,15 +138,33 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // --------------------------------------------------------------------------------------------
 // bf16 MFMA kernel
 // --------------------------------------------------------------------------------------------
-constexpr int BK = 64;          // K elements per stage
-constexpr int ROWB = BK * 2;    // bytes per tile row in LDS
 constexpr int BROWS = 256;      // weight rows per block tile
+constexpr int BK = 64;          // K elements per stage
+constexpr int ROWB = BK * 2;    // bytes per tile row in LDS (eight 16-byte chunks)
 
+// Chunk swizzle of a 128-byte tile row: XOR with the row so that 16 consecutive rows x one
+// logical chunk cover a 256-byte bank window exactly once.
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int BM, bool GATED, int WM, int WN>
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N <= 20, "vmcnt immediate");
+#define MOE_VMCNT_CASE(n) \
+  if constexpr (N == n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory");
+  MOE_VMCNT_CASE(0) MOE_VMCNT_CASE(1) MOE_VMCNT_CASE(2) MOE_VMCNT_CASE(3) MOE_VMCNT_CASE(4)
+  MOE_VMCNT_CASE(5) MOE_VMCNT_CASE(6) MOE_VMCNT_CASE(7) MOE_VMCNT_CASE(8) MOE_VMCNT_CASE(9)
+  MOE_VMCNT_CASE(10) MOE_VMCNT_CASE(11) MOE_VMCNT_CASE(12) MOE_VMCNT_CASE(13) MOE_VMCNT_CASE(14)
+  MOE_VMCNT_CASE(15) MOE_VMCNT_CASE(16) MOE_VMCNT_CASE(17) MOE_VMCNT_CASE(18) MOE_VMCNT_CASE(19)
+  MOE_VMCNT_CASE(20)
+#undef MOE_VMCNT_CASE
+}
+
+// BM x 256 block tile, WM x WN waves, NSTAGE LDS stages of 64 K-elements.
+// NSTAGE == 2: hand-ordered double-buffered pipeline (large tiles, MFMA/L2 bound).
+// NSTAGE  > 2: ring with NSTAGE-1 stages of loads in flight (small tiles, latency bound).
+template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int NW = WM * WN;                     // waves per block
+  constexpr int KSTEPS = BK / 16;                 // MFMA k-steps per stage
   constexpr int MI = BM / WM / 32;                // 32-row activation sub-tiles per wave
   constexpr int NI = BROWS / WN / 32;             // 32-row weight sub-tiles per wave
   constexpr int NIH = GATED ? NI / 2 : NI;        // gated: sub-tiles per weight matrix
@@ -130,24 +174,30 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int NLB = 128 / 8 / NW;               // ... per 128 weight rows
   constexpr int BN_OUT = GATED ? 128 : 256;       // output columns per block tile
   static_assert(NLA * 8 * NW == BM && NLB * 8 * NW == 128 && MI >= 1 && NIH >= 1, "tile shape");
+  static_assert(KSTEPS == 4, "the pipelines below are written for four k-steps per stage");
   extern __shared__ __align__(1024) unsigned char lds[];
 
   TileCoord tc;
-  if (!decode_tile(p.offsets, p.E, BM, p.n_tiles, p.rows, tc)) return;
+  if (!decode_tile(p, tc)) return;
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   const int wm = wave / WN, wn = wave % WN;
   const int K = p.K, N = p.N;
+  const int KT = K / BK;
   const int n0 = tc.n_tile * BN_OUT;
   const bf16_t* A = static_cast<const bf16_t*>(p.a);
   const bf16_t* B0 = static_cast<const bf16_t*>(p.b0) + static_cast<int64_t>(tc.e) * N * K;
   const bf16_t* B1 = GATED ? static_cast<const bf16_t*>(p.b1) + static_cast<int64_t>(tc.e) * N * K
                            : nullptr;
+  // 32-row activation sub-tiles of this wave that hold at least one valid row
+  const int rows_valid = min(tc.m_end - tc.m_begin, BM);
+  const int mi_valid = max(0, min(MI, (rows_valid - wm * (BM / WM) + 31) / 32));
 
-  // ---- global -> LDS assignment: instruction i of this wave fills row group g = i*NW + wave.
-  //      Which matrix a row group belongs to depends on i alone, so each instruction has a
-  //      uniform 64-bit base and a 32-bit per-lane offset.
+  // ---- global -> LDS assignment: instruction i of this wave fills row group g = i*NW + wave
+  //      (8 rows x 8 chunks = 1 KiB).  Which matrix a row group belongs to depends on i alone,
+  //      so each instruction has a uniform 64-bit base and a 32-bit per-lane offset.  Rows past
+  //      the end of the segment (or of the weight matrix) re-read the last valid row.
   const unsigned char* base_a =
       reinterpret_cast<const unsigned char*>(A + static_cast<int64_t>(tc.m_begin) * K);
   const unsigned char* base_b0 =
@@ -159,41 +209,34 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   for (int i = 0; i < NLOAD; ++i) {
     const int g = i * NW + wave;
     const int row = g * 8 + (lane >> 3);          // row in the stage: [0,BM) x rows, then weights
-    const int chunk = (lane & 7) ^ swz(row);      // the 16 B chunk of the row this lane fetches
+    const int chunk = (lane & 7) ^ swz(row);      // the chunk of the row this lane fetches
     int r;                                        // row relative to the instruction's base
     if (i < NLA) {
-      r = min(row, tc.m_end - 1 - tc.m_begin);
+      r = min(row, rows_valid - 1);
     } else {
       const int br = row - BM;
       r = GATED ? min(br & 127, N - 1 - n0) : min(br, N - 1 - n0);
     }
     soff[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
   }
-  auto issue_loads = [&](int kt, int stage) {
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) {
-      const int g = i * NW + wave;
-      const unsigned char* base =
-          (i < NLA) ? base_a : (!GATED || i < NLA + NLB) ? base_b0 : base_b1;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(base + static_cast<int64_t>(kt) * ROWB + soff[i]),
-          (__attribute__((address_space(3))) void*)(lds + stage * STAGE + g * 1024), 16, 0, 0);
-    }
+  auto issue_load = [&](int i, int kt, int stage) {
+    const int g = i * NW + wave;
+    const unsigned char* base = (i < NLA) ? base_a : (!GATED || i < NLA + NLB) ? base_b0 : base_b1;
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(base + static_cast<int64_t>(kt) * ROWB + soff[i]),
+        (__attribute__((address_space(3))) void*)(lds + stage * STAGE + g * 1024), 16, 0, 0);
   };
 
   // ---- LDS read addresses of the MFMA fragments ------------------------------------------------
   const int l32 = lane & 31;
   const int f = swz(lane);                        // sub-tile bases are multiples of 32 rows
-  int koff[4];
+  int koff[KSTEPS];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) koff[kk] = (((kk * 2 + (lane >> 5)) ^ f) << 4);
+  for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = (((kk * 2 + (lane >> 5)) ^ f) << 4);
   const int x_base = (wm * (BM / WM) + l32) * ROWB;
-  int w_sub[NI];                                  // first weight row of sub-tile ni in the stage
-#pragma unroll
-  for (int ni = 0; ni < NI; ++ni)
-    w_sub[ni] = GATED ? (ni / NIH) * 128 + wn * (NIH * 32) + (ni % NIH) * 32
-                      : wn * (NI * 32) + ni * 32;
-  const int w_base = (BM + l32) * ROWB;
+  // first weight row of sub-tile ni relative to the wave's own first weight row
+  auto w_sub = [](int ni) { return GATED ? (ni / NIH) * 128 + (ni % NIH) * 32 : ni * 32; };
+  const int w_base = (BM + (GATED ? wn * (NIH * 32) : wn * (NI * 32)) + l32) * ROWB;
 
   f32x16_t acc[NI][MI];
 #pragma unroll
@@ -203,50 +246,147 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
 
-  auto load_frags = [&](const unsigned char* sb, int kk, bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
+  // compiler-scheduled stage: used for partial tiles and by the ring pipeline
+  auto compute_guarded = [&](int stage) {
+    const unsigned char* sb = lds + stage * STAGE;
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-      xf[mi] = *reinterpret_cast<const bf16x8_t*>(sb + x_base + mi * 32 * ROWB + koff[kk]);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
-      wf[ni] = *reinterpret_cast<const bf16x8_t*>(sb + w_base + w_sub[ni] * ROWB + koff[kk]);
-  };
-  auto mma = [&](const bf16x8_t (&xf)[MI], const bf16x8_t (&wf)[NI]) {
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      bf16x8_t xf[MI], wf[NI];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
-        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
-  };
-  // one stage = 4 MFMA k-steps; the fragments of step kk+1 are read while step kk multiplies
-  auto compute = [&](int stage) {
-    const unsigned char* sb = lds + stage * STAGE;
-    bf16x8_t xa[MI], wa[NI], xb[MI], wb[NI];
-    load_frags(sb, 0, xa, wa);
-    load_frags(sb, 1, xb, wb);
-    mma(xa, wa);
-    load_frags(sb, 2, xa, wa);
-    mma(xb, wb);
-    load_frags(sb, 3, xb, wb);
-    mma(xa, wa);
-    mma(xb, wb);
+        if (mi < mi_valid)
+          xf[mi] = *reinterpret_cast<const bf16x8_t*>(sb + x_base + mi * 32 * ROWB + koff[kk]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        wf[ni] = *reinterpret_cast<const bf16x8_t*>(sb + w_base + w_sub(ni) * ROWB + koff[kk]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          if (mi < mi_valid)
+            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+    }
   };
 
-  const int KT = K / BK;
-  issue_loads(0, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  for (int kt = 0; kt < KT; kt += 2) {
-    if (kt + 1 < KT) issue_loads(kt + 1, 1);
-    compute(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < KT) {
-      if (kt + 2 < KT) issue_loads(kt + 2, 0);
-      compute(1);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
+  if constexpr (NSTAGE > 2) {
+    // ---- ring pipeline: the loads of stage kt+DIST are issued at the start of stage kt -------
+    constexpr int DIST = NSTAGE - 1;
+#pragma unroll
+    for (int s = 0; s < DIST; ++s)
+      if (s < KT) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) issue_load(i, s, s);
+      }
+    for (int kt = 0; kt < KT; ++kt) {
+      // the loads of stage kt are the oldest outstanding; up to DIST-1 later stages may follow
+      const int later = min(DIST - 1, KT - 1 - kt);
+      if (later >= 2) wait_vmcnt<2 * NLOAD>();
+      else if (later == 1) wait_vmcnt<NLOAD>();
+      else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();     // stage kt landed for all waves; the slot of kt-1 is free
+      asm volatile("" ::: "memory");
+      if (kt + DIST < KT) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) issue_load(i, kt + DIST, (kt + DIST) % NSTAGE);
+      }
+      if (mi_valid > 0) compute_guarded(kt % NSTAGE);
     }
+  } else if (mi_valid < MI) {
+    // ---- two stages, partial tile: same barrier protocol as the full path below ----------------
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) issue_load(i, 0, 0);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    for (int kt = 0; kt < KT; ++kt) {
+      if (kt + 1 < KT) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) issue_load(i, kt + 1, (kt + 1) & 1);
+      }
+      if (mi_valid > 0) compute_guarded(kt & 1);
+      wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
+  } else {
+    // ---- two stages, full tile: hand-ordered pipeline --------------------------------------------
+    // Two fragment register sets (A, B) alternate over the four k-steps of a stage: the LDS reads
+    // of step kk+1 are in flight while step kk multiplies.  The global->LDS loads of the next
+    // stage are issued in two groups early in the stage so that they have most of the stage to
+    // land.  Inline asm pins the order; waits are explicit (the compiler does not see these LDS
+    // reads, so it inserts none of its own).
+    int xad[2][KSTEPS], wad[2][KSTEPS];       // per stage buffer, per k-step LDS byte addresses
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        xad[st][kk] = st * STAGE + x_base + koff[kk];
+        wad[st][kk] = st * STAGE + w_base + koff[kk];
+      }
+    bf16x8_t xA[MI], wA[NI], xB[MI], wB[NI];
+#define MOE_RD(dst, addr, off) \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
+#define MOE_MFMA(c, w, x) \
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
+    auto read_frags = [&](bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI], int xa, int wa) {
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) MOE_RD(xf[mi], xa, mi * 32 * ROWB);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+        MOE_RD(wf[ni], wa, (GATED ? (ni / NIH) * 128 + (ni % NIH) * 32 : ni * 32) * ROWB);
+    };
+    auto mma = [&](bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xf[mi]);
+    };
+    auto stage_body = [&](int kt, auto cur_c) {
+      constexpr int CUR = decltype(cur_c)::value;
+      const bool more = kt + 1 < KT;
+      constexpr int G0 = (NLOAD + 1) / 2;           // load groups [0,G0) and [G0,NLOAD)
+      if (more) {
+#pragma unroll
+        for (int i = 0; i < G0; ++i) issue_load(i, kt + 1, CUR ^ 1);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      read_frags(xB, wB, xad[CUR][1], wad[CUR][1]);
+      mma(xA, wA);                                  // k-step 0
+      if (more) {
+#pragma unroll
+        for (int i = G0; i < NLOAD; ++i) issue_load(i, kt + 1, CUR ^ 1);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      read_frags(xA, wA, xad[CUR][2], wad[CUR][2]);
+      mma(xB, wB);                                  // k-step 1
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      read_frags(xB, wB, xad[CUR][3], wad[CUR][3]);
+      mma(xA, wA);                                  // k-step 2
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      mma(xB, wB);                                  // k-step 3
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();                 // next stage landed everywhere; this one is free
+      asm volatile("" ::: "memory");
+      if (more) read_frags(xA, wA, xad[CUR ^ 1][0], wad[CUR ^ 1][0]);
+    };
+
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) issue_load(i, 0, 0);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    read_frags(xA, wA, xad[0][0], wad[0][0]);
+    int kt = 0;
+    for (; kt + 1 < KT; kt += 2) {
+      stage_body(kt, std::integral_constant<int, 0>{});
+      stage_body(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) stage_body(kt, std::integral_constant<int, 0>{});
+    // the compiler's hazard handling does not see asm MFMAs: let the last results retire
+    // before ordinary VALU code reads the accumulators
+    asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+#undef MOE_RD
+#undef MOE_MFMA
   }
 
   // ---- epilogue: accumulator (v, lane) holds out[row = m-sub-tile + lane%32]
@@ -295,7 +435,7 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
   __shared__ float As[TK][TM + 4];
   __shared__ float Bs[GATED ? 2 : 1][TK][TN + 4];
   TileCoord tc;
-  if (!decode_tile(p.offsets, p.E, TM, p.n_tiles, p.rows, tc)) return;
+  if (!decode_tile(p, tc)) return;
   const int K = p.K, N = p.N;
   const int n0 = tc.n_tile * TN;
   const T* A = static_cast<const T*>(p.a);
@@ -363,33 +503,39 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
   }
 }
 
-// Upper bound on sum_e ceil(count_e / BM) that needs no knowledge of the counts.
-static int64_t max_m_tiles(int64_t A, int E, int BM) {
-  const int64_t ub = A / BM + E;
-  return ub < A ? ub : A;
+// Upper bounds on the number of m-tiles that need no knowledge of the counts:
+// every expert has at most floor(c/bm) full tiles (sum <= A/bm) and one remainder.
+static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
+  const int64_t e_cap = E < A ? E : A;
+  if (mode == TILES_SMALL) return e_cap;
+  return A / bm + e_cap;
 }
 
-template <int BM, bool GATED, int WM, int WN>
-static int launch_mfma(const GemmArgs& a, int64_t A, hipStream_t st) {
-  constexpr int lds_bytes = 2 * (BM + BROWS) * ROWB;
+template <int BM, bool GATED, int WM, int WN, int NSTAGE>
+static int launch_mfma(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t st) {
+  constexpr int lds_bytes = NSTAGE * (BM + BROWS) * ROWB;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
       return MOE_ERR_HIP;
     attr_set = true;
   }
-  int64_t grid = max_m_tiles(A, a.E, BM) * a.n_tiles;
+  a.mode = mode;
+  a.bm_main = bm_main;
+  int64_t grid = max_m_tiles(A, a.E, bm_main, mode) * a.n_tiles;
   grid = (grid + 7) / 8 * 8;
   if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((ffn_mfma_kernel<BM, GATED, WM, WN>), dim3(static_cast<unsigned>(grid)),
+  hipLaunchKernelGGL((ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>), dim3(static_cast<unsigned>(grid)),
                      dim3(WM * WN * 64), lds_bytes, st, a);
   return launch_status();
 }
 
 template <typename T, bool GATED>
-static int launch_generic(const GemmArgs& a, int64_t A, hipStream_t st) {
-  int64_t grid = max_m_tiles(A, a.E, 64) * a.n_tiles;
+static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
+  a.mode = TILES_ALL;
+  a.bm_main = 64;
+  int64_t grid = max_m_tiles(A, a.E, 64, TILES_ALL) * a.n_tiles;
   grid = (grid + 7) / 8 * 8;
   if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
   hipLaunchKernelGGL((ffn_generic_kernel<T, GATED>), dim3(static_cast<unsigned>(grid)), dim3(256), 0,
@@ -397,13 +543,20 @@ static int launch_generic(const GemmArgs& a, int64_t A, hipStream_t st) {
   return launch_status();
 }
 
-}  // namespace moe
+// One grouped GEMM on the MFMA path: main tiles, then the small remainders.
+template <bool GATED>
+static int mfma_gemm(const GemmArgs& g, int64_t A, hipStream_t st) {
+  const bool big = A / g.E >= 512;   // mean rows per expert
+  int rc = big ? launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st)
+               : launch_mfma<128, GATED, 2, 4, 2>(g, TILES_MAIN, 128, A, st);
+  if (rc != MOE_OK) return rc;
+  return launch_mfma<64, GATED, 2, 4, 4>(g, TILES_SMALL, big ? 256 : 128, A, st);
+}
 
 // parts: bit 0 = gated up-projection (h), bit 1 = down-projection (y_perm)
 static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
                             const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
                             int parts, void* hip_stream) {
-  using namespace moe;
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
@@ -414,19 +567,17 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t A = static_cast<int64_t>(shape->T) * shape->k;
   const int d = shape->d, F = shape->F, E = shape->E;
-  GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A)};
-  GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A)};
+  GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_ALL, 64};
+  GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_ALL, 64};
   const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
     g2.n_tiles = (d + 255) / 256;
-    const bool big = A / E >= 512;
     if (up) {
-      rc = big ? launch_mfma<256, true, 4, 2>(g1, A, st) : launch_mfma<128, true, 2, 4>(g1, A, st);
+      rc = mfma_gemm<true>(g1, A, st);
       if (rc != MOE_OK) return rc;
     }
-    if (down)
-      rc = big ? launch_mfma<256, false, 4, 2>(g2, A, st) : launch_mfma<128, false, 2, 4>(g2, A, st);
+    if (down) rc = mfma_gemm<false>(g2, A, st);
     return rc;
   }
   g1.n_tiles = (F + 63) / 64;
@@ -447,10 +598,12 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   return rc;
 }
 
+}  // namespace moe
+
 extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
                                const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
                                void* hip_stream) {
-  return grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
+  return moe::grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
 }
 
 extern "C" int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm,
@@ -458,5 +611,5 @@ extern "C" int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm
                                     const void* w2, void* h, void* y_perm, int part,
                                     void* hip_stream) {
   if (part != 1 && part != 2) return MOE_ERR_INVALID_ARG;
-  return grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, hip_stream);
+  return moe::grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, hip_stream);
 }
