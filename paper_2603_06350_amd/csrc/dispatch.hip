@@ -168,10 +168,11 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ x
   if (lane < k) my_dst = dst_row[static_cast<int64_t>(t) * k + lane];
   if (static_cast<unsigned>(my_dst) >= static_cast<unsigned>(A)) my_dst = 0;
   const uint4* src = x + static_cast<int64_t>(t) * row16;
-  for (int c0 = 0; c0 < row16; c0 += 4 * MOE_WAVE) {
-    uint4 v[4];
+  constexpr int UNR = 4;   // 16-byte loads in flight per lane (4 KiB per wave)
+  for (int c0 = 0; c0 < row16; c0 += UNR * MOE_WAVE) {
+    uint4 v[UNR];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < UNR; ++u) {
       const int c = c0 + u * MOE_WAVE + lane;
       if (c < row16) v[u] = src[c];
     }
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ x
       const int dst = __shfl(my_dst, j);
       uint4* out = x_perm + static_cast<int64_t>(dst) * row16;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < UNR; ++u) {
         const int c = c0 + u * MOE_WAVE + lane;
         if (c < row16) out[c] = v[u];
       }

@@ -6,16 +6,19 @@
 // runs v_mfma_f32_16x16x32_bf16 on its slice straight from global memory (x is
 // read exactly once from HBM, 16 B per lane; w_gate is small and stays in L2), the
 // eight partial score tiles meet in LDS and are summed in a fixed order, so the
-// scores are deterministic.  Each wave then routes two tokens with a
-// cross-lane butterfly arg-max (value descending, expert index ascending), k+1
-// times, and derives the softmax weights from the same scores.
+// scores are deterministic.  Each wave then routes two tokens by rank counting:
+// every lane compares its scores with all E scores (broadcast LDS reads), and the
+// expert preceded by r others (larger score, or equal score and lower index) is the
+// r-th pick; the softmax weights come from the same scores.
 //
 // The integer choice must not depend on the order of an fp32 sum.  After the fast
-// pass a token is "ambiguous" if two neighbours among its leading k+1 scores are
-// closer than 2^-14 * max|logit| (plus a few ulps of the scores themselves).
-// Such tokens (about 1% for 64 experts, ~0.03% for 8) are re-evaluated by the
-// whole block with exact products and fp64 sums, rounded once to fp32, which is the
-// correctly rounded score up to fp64 rounding; fp32 inputs always take this path.
+// pass a token is "ambiguous" if one of its k chosen scores has another score within
+// 2^-14 * max|logit| (plus a few ulps of the score itself).  For such tokens (about
+// 1% for 64 experts, ~0.03% for 8) the whole block re-scores the experts that could
+// still be among the first k (at most 16; all E if there are more) with exact
+// products and fp64 sums rounded once to fp32, which is the correctly rounded score
+// up to fp64 rounding, and the token is routed again.  fp32 inputs always take the
+// exact path for all experts.
 #include "moe_internal.h"
 
 namespace moe {
@@ -26,18 +29,8 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 constexpr int RT_TM = 16;
 constexpr int RT_NW = 8;
 constexpr int RT_THREADS = RT_NW * MOE_WAVE;
+constexpr int RT_BATCH = 8;   // MFMA steps whose x fragments are requested together
 
-__device__ __forceinline__ void wave_argmax(float& v, int& i) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const float ov = __shfl_xor(v, off);
-    const int oi = __shfl_xor(i, off);
-    if (ov > v || (ov == v && oi < i)) {
-      v = ov;
-      i = oi;
-    }
-  }
-}
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
@@ -49,74 +42,176 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// Routes one token with a full wave.  s[q] is the score of expert lane + 64 q.
-// With `check`, returns true (and writes nothing) if the order of the leading k+1
-// scores is not safely decided at the fast pass's accuracy.
+constexpr int RT_CMAX = 16;   // candidate experts re-scored exactly for an ambiguous token
+
+// Value of s[q] in the lane/slot where hit[q] is true (exactly one such slot is expected);
+// `dflt` if there is none.  Wave-uniform result.
 template <int QE>
-__device__ bool route_token(const float (&s)[QE], float lmax, bool check, int E, int k, int renorm,
-                            int64_t t, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                            float* __restrict__ scores_out) {
+__device__ __forceinline__ float pick_where(const float (&s)[QE], const bool (&hit)[QE], float dflt) {
+  float r = dflt;
+#pragma unroll
+  for (int q = 0; q < QE; ++q) {
+    const unsigned long long m = __ballot(hit[q]);
+    if (m != 0ull) r = __shfl(s[q], __ffsll(static_cast<long long>(m)) - 1);
+  }
+  return r;
+}
+
+// Routes one token with a full wave.  s[q] is the score of expert lane + 64 q; srow is a
+// per-wave LDS row of at least (E rounded up to 4) floats.
+// Selection by rank counting: every lane compares its scores with all E scores (broadcast LDS
+// reads, no cross-lane dependency chain); the expert whose score is preceded by r others
+// (larger score, or equal score and lower index) is the r-th pick.
+// With `check`: if any of the k chosen experts has another score within the fast pass's error
+// margin, nothing is written; the experts that could still be among the first k are listed in
+// cand[] and their number is returned (RT_CMAX + 1 if there are too many).  Otherwise returns 0.
+template <int QE>
+__device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, int k, int renorm,
+                           int64_t t, float* __restrict__ srow, int* __restrict__ cand,
+                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                           float* __restrict__ scores_out) {
   const int lane = lane_id();
-  bool taken[QE];
+  const int e4 = (E + 3) & ~3;
 #pragma unroll
-  for (int q = 0; q < QE; ++q) taken[q] = false;
-  float sel_v = 0.f;
-  int sel_i = 0;
-  float next_v = 0.f;  // the (k+1)-th largest score (only when E > k)
-  const int npick = (check && E > k) ? k + 1 : k;
-  for (int j = 0; j < npick; ++j) {
-    float v = -INFINITY;
-    int i = 0x7FFFFFFF;
+  for (int q = 0; q < QE; ++q) {
+    const int e = lane + MOE_WAVE * q;
+    if (e < e4) srow[e] = (e < E) ? s[q] : -INFINITY;
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: LDS writes land before the reads
+  int rank[QE];
+  float mingap[QE];
 #pragma unroll
-    for (int q = 0; q < QE; ++q) {
-      const int e = lane + MOE_WAVE * q;
-      if (e < E && !taken[q] && (s[q] > v || (s[q] == v && e < i))) {
-        v = s[q];
-        i = e;
+  for (int q = 0; q < QE; ++q) {
+    rank[q] = 0;
+    mingap[q] = INFINITY;
+  }
+#pragma unroll 4
+  for (int e2 = 0; e2 < e4; e2 += 4) {
+    const float4 v4 = *reinterpret_cast<const float4*>(srow + e2);
+    const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+      for (int q = 0; q < QE; ++q) {
+        const int e = lane + MOE_WAVE * q;
+        rank[q] += (v[u] > s[q] || (v[u] == s[q] && e2 + u < e)) ? 1 : 0;
+        if (e2 + u != e) mingap[q] = fminf(mingap[q], fabsf(v[u] - s[q]));
       }
     }
-    wave_argmax(v, i);
-    if (j < k) {
-      if (lane == j) {
-        sel_v = v;
-        sel_i = i;
-      }
-    } else {
-      next_v = v;
-    }
+  }
+  bool valid[QE], chosen[QE];
 #pragma unroll
-    for (int q = 0; q < QE; ++q)
-      if (i == lane + MOE_WAVE * q) taken[q] = true;
+  for (int q = 0; q < QE; ++q) {
+    valid[q] = lane + MOE_WAVE * q < E;
+    chosen[q] = valid[q] && rank[q] < k;
   }
   if (check) {
-    float below = __shfl_down(sel_v, 1);
-    if (lane == k - 1) below = next_v;
-    const bool has_below = (lane < k - 1) || (lane == k - 1 && E > k);
-    const float tol = 6.103515625e-05f * lmax + 4.76837158203125e-07f * fmaxf(fabsf(sel_v), fabsf(below));
-    const bool amb = has_below && !(sel_v - below > tol);
-    if (__ballot(amb) != 0ull) return true;
-  }
-  const float m = __shfl(sel_v, 0);
-  float p = 0.f;
+    bool amb = false;
 #pragma unroll
-  for (int q = 0; q < QE; ++q)
-    if (lane + MOE_WAVE * q < E) p += expf(s[q] - m);
-  const float denom = wave_sum(p);
-  float w = (lane < k) ? expf(sel_v - m) / denom : 0.f;
-  if (renorm) {
-    const float ws = wave_sum(w);
-    w = w / ws;
-  }
-  if (lane < k) {
-    topk_idx[t * k + lane] = (static_cast<unsigned>(sel_i) < static_cast<unsigned>(E)) ? sel_i : 0;
-    topk_w[t * k + lane] = w;
-  }
-  if (scores_out) {
+    for (int q = 0; q < QE; ++q) {
+      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(s[q]);
+      amb = amb || (chosen[q] && !(mingap[q] > tol));
+    }
+    if (__ballot(amb) != 0ull) {
+      // candidates: every expert whose score is not clearly below the k-th pick's neighbourhood
+      bool is_kth[QE];
 #pragma unroll
-    for (int q = 0; q < QE; ++q)
-      if (lane + MOE_WAVE * q < E) scores_out[t * E + lane + MOE_WAVE * q] = s[q];
+      for (int q = 0; q < QE; ++q) is_kth[q] = valid[q] && rank[q] == (E > k ? k : k - 1);
+      const float thr = pick_where<QE>(s, is_kth, -INFINITY);
+      const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(thr));
+      int n = 0;
+#pragma unroll
+      for (int q = 0; q < QE; ++q) {
+        const bool c = valid[q] && s[q] >= thr - margin;
+        const unsigned long long m = __ballot(c);
+        const int pos = n + __popcll(m & ((1ull << lane) - 1ull));
+        if (c && pos < RT_CMAX) cand[pos] = lane + MOE_WAVE * q;
+        n += __popcll(m);
+      }
+      return n <= RT_CMAX ? n : RT_CMAX + 1;
+    }
   }
-  return false;
+  bool is_top[QE];
+#pragma unroll
+  for (int q = 0; q < QE; ++q) is_top[q] = valid[q] && rank[q] == 0;
+  const float m = pick_where<QE>(s, is_top, 0.f);
+  float p[QE];
+  float psum = 0.f;
+#pragma unroll
+  for (int q = 0; q < QE; ++q) {
+    p[q] = valid[q] ? expf(s[q] - m) : 0.f;
+    psum += p[q];
+  }
+  const float denom = wave_sum(psum);
+  float wsel = 0.f;
+#pragma unroll
+  for (int q = 0; q < QE; ++q) {
+    p[q] = p[q] / denom;
+    wsel += chosen[q] ? p[q] : 0.f;
+  }
+  const float ws = renorm ? wave_sum(wsel) : 1.0f;
+#pragma unroll
+  for (int q = 0; q < QE; ++q) {
+    if (chosen[q]) {
+      topk_idx[t * k + rank[q]] = lane + MOE_WAVE * q;
+      topk_w[t * k + rank[q]] = renorm ? p[q] / ws : p[q];
+    }
+    if (scores_out && valid[q]) scores_out[t * E + lane + MOE_WAVE * q] = s[q];
+  }
+  return 0;
+}
+
+// Exact gate sums (fp64) of one token for up to RT_CMAX listed experts, this wave's part of the
+// hidden dimension.  Lane = (candidate slot, one of four sub-slices).
+template <bool BF16>
+__device__ void exact_candidates(const uint4* __restrict__ xrow, const uint4* __restrict__ wg,
+                                 int row16, const int* __restrict__ cand, int n, int wave,
+                                 double* __restrict__ dpart) {
+  const int lane = lane_id();
+  const int c = lane & (RT_CMAX - 1);
+  const int sub = lane / RT_CMAX;
+  constexpr int NSUB = MOE_WAVE / RT_CMAX;
+  const int e = cand[c < n ? c : 0];
+  const uint4* wrow = wg + static_cast<int64_t>(e) * row16;
+  const int cw = (row16 + RT_NW - 1) / RT_NW;
+  const int c0 = wave * cw;
+  const int c1 = min(row16, c0 + cw);
+  double acc = 0.0;
+  constexpr int XB = 8;
+  for (int cb = c0 + sub; cb < c1; cb += XB * NSUB) {
+    uint4 av[XB], bv[XB];
+#pragma unroll
+    for (int u = 0; u < XB; ++u) {
+      const int cc = min(cb + u * NSUB, row16 - 1);
+      av[u] = xrow[cc];
+      bv[u] = wrow[cc];
+    }
+#pragma unroll
+    for (int u = 0; u < XB; ++u) {
+      if (cb + u * NSUB < c1) {
+        const uint4 a = av[u];
+        const uint4 b = bv[u];
+        if (BF16) {
+          acc = fma(static_cast<double>(bf16lo(a.x)), static_cast<double>(bf16lo(b.x)), acc);
+          acc = fma(static_cast<double>(bf16hi(a.x)), static_cast<double>(bf16hi(b.x)), acc);
+          acc = fma(static_cast<double>(bf16lo(a.y)), static_cast<double>(bf16lo(b.y)), acc);
+          acc = fma(static_cast<double>(bf16hi(a.y)), static_cast<double>(bf16hi(b.y)), acc);
+          acc = fma(static_cast<double>(bf16lo(a.z)), static_cast<double>(bf16lo(b.z)), acc);
+          acc = fma(static_cast<double>(bf16hi(a.z)), static_cast<double>(bf16hi(b.z)), acc);
+          acc = fma(static_cast<double>(bf16lo(a.w)), static_cast<double>(bf16lo(b.w)), acc);
+          acc = fma(static_cast<double>(bf16hi(a.w)), static_cast<double>(bf16hi(b.w)), acc);
+        } else {
+          acc = fma(static_cast<double>(__uint_as_float(a.x)), static_cast<double>(__uint_as_float(b.x)), acc);
+          acc = fma(static_cast<double>(__uint_as_float(a.y)), static_cast<double>(__uint_as_float(b.y)), acc);
+          acc = fma(static_cast<double>(__uint_as_float(a.z)), static_cast<double>(__uint_as_float(b.z)), acc);
+          acc = fma(static_cast<double>(__uint_as_float(a.w)), static_cast<double>(__uint_as_float(b.w)), acc);
+        }
+      }
+    }
+  }
+  acc += __shfl_xor(acc, 16);
+  acc += __shfl_xor(acc, 32);
+  if (sub == 0 && c < n) dpart[wave * RT_CMAX + c] = acc;
 }
 
 // Exact partial gate sums of one token over this wave's part of the hidden
@@ -140,23 +235,38 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
     const int e_ld = min(e, E - 1);
     const uint4* wrow = wg + static_cast<int64_t>(e_ld) * row16;
     double acc = 0.0;
-    for (int c = c0 + sub; c < c1; c += nsub) {
-      const uint4 a = xrow[c];
-      const uint4 b = wrow[c];
-      if (BF16) {
-        acc = fma(static_cast<double>(bf16lo(a.x)), static_cast<double>(bf16lo(b.x)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.x)), static_cast<double>(bf16hi(b.x)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.y)), static_cast<double>(bf16lo(b.y)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.y)), static_cast<double>(bf16hi(b.y)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.z)), static_cast<double>(bf16lo(b.z)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.z)), static_cast<double>(bf16hi(b.z)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.w)), static_cast<double>(bf16lo(b.w)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.w)), static_cast<double>(bf16hi(b.w)), acc);
-      } else {
-        acc = fma(static_cast<double>(__uint_as_float(a.x)), static_cast<double>(__uint_as_float(b.x)), acc);
-        acc = fma(static_cast<double>(__uint_as_float(a.y)), static_cast<double>(__uint_as_float(b.y)), acc);
-        acc = fma(static_cast<double>(__uint_as_float(a.z)), static_cast<double>(__uint_as_float(b.z)), acc);
-        acc = fma(static_cast<double>(__uint_as_float(a.w)), static_cast<double>(__uint_as_float(b.w)), acc);
+    // eight chunk pairs are requested before the first is used (the loads are L2/HBM round
+    // trips; the fp64 sum order stays ascending in c)
+    constexpr int XB = 8;
+    for (int cb = c0 + sub; cb < c1; cb += XB * nsub) {
+      uint4 av[XB], bv[XB];
+#pragma unroll
+      for (int u = 0; u < XB; ++u) {
+        const int c = min(cb + u * nsub, row16 - 1);
+        av[u] = xrow[c];
+        bv[u] = wrow[c];
+      }
+#pragma unroll
+      for (int u = 0; u < XB; ++u) {
+        if (cb + u * nsub < c1) {
+          const uint4 a = av[u];
+          const uint4 b = bv[u];
+          if (BF16) {
+            acc = fma(static_cast<double>(bf16lo(a.x)), static_cast<double>(bf16lo(b.x)), acc);
+            acc = fma(static_cast<double>(bf16hi(a.x)), static_cast<double>(bf16hi(b.x)), acc);
+            acc = fma(static_cast<double>(bf16lo(a.y)), static_cast<double>(bf16lo(b.y)), acc);
+            acc = fma(static_cast<double>(bf16hi(a.y)), static_cast<double>(bf16hi(b.y)), acc);
+            acc = fma(static_cast<double>(bf16lo(a.z)), static_cast<double>(bf16lo(b.z)), acc);
+            acc = fma(static_cast<double>(bf16hi(a.z)), static_cast<double>(bf16hi(b.z)), acc);
+            acc = fma(static_cast<double>(bf16lo(a.w)), static_cast<double>(bf16lo(b.w)), acc);
+            acc = fma(static_cast<double>(bf16hi(a.w)), static_cast<double>(bf16hi(b.w)), acc);
+          } else {
+            acc = fma(static_cast<double>(__uint_as_float(a.x)), static_cast<double>(__uint_as_float(b.x)), acc);
+            acc = fma(static_cast<double>(__uint_as_float(a.y)), static_cast<double>(__uint_as_float(b.y)), acc);
+            acc = fma(static_cast<double>(__uint_as_float(a.z)), static_cast<double>(__uint_as_float(b.z)), acc);
+            acc = fma(static_cast<double>(__uint_as_float(a.w)), static_cast<double>(__uint_as_float(b.w)), acc);
+          }
+        }
       }
     }
     for (int off = ep; off < MOE_WAVE; off <<= 1) acc += __shfl_xor(acc, off);
@@ -164,7 +274,8 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
   }
 }
 
-// Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][E] | int flag[RT_TM]
+// Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][max(E,RT_CMAX)] |
+//              float srow[RT_NW][E4] | int cand[RT_TM][RT_CMAX] | int flag[RT_TM]      (E4 = E rounded up to 4)
 template <bool BF16, int NT>
 __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
@@ -173,12 +284,34 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);
+  const int e4 = (E + 3) & ~3;
+  const int dn = E > RT_CMAX ? E : RT_CMAX;
   double* dpart = reinterpret_cast<double*>(smem + static_cast<size_t>(RT_NW) * RT_TM * E * 4);
-  int* flag = reinterpret_cast<int*>(dpart + RT_NW * E);
+  float* srow_all = reinterpret_cast<float*>(dpart + RT_NW * dn);
+  int* cand_all = reinterpret_cast<int*>(srow_all + RT_NW * e4);
+  int* flag = cand_all + RT_TM * RT_CMAX;
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
   const int t0 = blockIdx.x * RT_TM;
   const int row16 = BF16 ? d / 8 : d / 4;
+  // fp32 scores of tile row `row` from the eight partial tiles (fixed order) plus the bias;
+  // returns the row's largest |logit| (before the bias)
+  auto fast_scores = [&](int row, float (&s)[QE]) -> float {
+    float la = 0.f;
+#pragma unroll
+    for (int q = 0; q < QE; ++q) {
+      const int e = lane + MOE_WAVE * q;
+      float v = 0.f;
+      if (e < E) {
+#pragma unroll
+        for (int w = 0; w < RT_NW; ++w) v += part[(w * RT_TM + row) * E + e];
+        la = fmaxf(la, fabsf(v));
+        if (bias) v += bias[e];
+      }
+      s[q] = v;
+    }
+    return wave_max(la);
+  };
 
   if (BF16) {
     // ---- fast pass: partial score tiles on the matrix cores ---------------------------------
@@ -196,21 +329,40 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
     const int c0 = wave * cw;
     const int c1 = min(row16, c0 + cw);
-#pragma unroll 2
-    for (int c = c0; c < c1; c += 4) {
-      const int cc = c + kq;
-      const bool valid = cc < row16;
-      const int cl = valid ? cc : row16 - 1;
-      uint4 a = xrow[cl];
-      if (!valid) a = make_uint4(0, 0, 0, 0);
-      uint4 b[NT];
+    // x comes from HBM and is read exactly once: a batch of RT_BATCH MFMA steps has all of its
+    // x fragments requested before the first one is used, so each wave keeps 8 KiB in flight.
+    // w_gate fragments come from L2 and are fetched per step.
+    for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
+      uint4 a[RT_BATCH];
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt) b[nt] = wrow[nt][cl];
+      for (int u = 0; u < RT_BATCH; ++u) {
+        const int cc = cb + 4 * u + kq;
+        a[u] = xrow[min(cc, row16 - 1)];
+      }
+      // w_gate fragments: BSTEPS steps' worth (16 loads) are requested together
+      constexpr int BSTEPS = NT >= 16 ? 1 : (NT <= 2 ? 8 : 16 / NT);
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                          __builtin_bit_cast(bf16x8_t, b[nt]),
-                                                          acc[nt], 0, 0, 0);
+      for (int u0 = 0; u0 < RT_BATCH; u0 += BSTEPS) {
+        uint4 b[BSTEPS][NT];
+#pragma unroll
+        for (int u = 0; u < BSTEPS; ++u) {
+          const int cl = min(cb + 4 * (u0 + u) + kq, row16 - 1);
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) b[u][nt] = wrow[nt][cl];
+        }
+#pragma unroll
+        for (int u = 0; u < BSTEPS; ++u) {
+          if (cb + 4 * (u0 + u) < c1) {                // wave-uniform
+            uint4 av = a[u0 + u];
+            if (cb + 4 * (u0 + u) + kq >= row16) av = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                                __builtin_bit_cast(bf16x8_t, b[u][nt]),
+                                                                acc[nt], 0, 0, 0);
+          }
+        }
+      }
     }
     // D layout of the 16x16 tile: lane holds expert column (lane & 15), token rows 4*(lane>>4)+v
 #pragma unroll
@@ -226,59 +378,71 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     for (int rr = 0; rr < RT_TM / RT_NW; ++rr) {
       const int row = wave * (RT_TM / RT_NW) + rr;
       const int t = t0 + row;
-      bool amb = false;
+      int amb = 0;
       if (t < T) {
         float s[QE];
-        float la = 0.f;
-#pragma unroll
-        for (int q = 0; q < QE; ++q) {
-          const int e = lane + MOE_WAVE * q;
-          float v = 0.f;
-          if (e < E) {
-#pragma unroll
-            for (int w = 0; w < RT_NW; ++w) v += part[(w * RT_TM + row) * E + e];
-            la = fmaxf(la, fabsf(v));
-            if (bias) v += bias[e];
-          }
-          s[q] = v;
-        }
-        const float lmax = wave_max(la);
-        amb = route_token<QE>(s, lmax, true, E, k, renorm, t, topk_idx, topk_w, scores_out);
+        const float lmax = fast_scores(row, s);
+        amb = route_token<QE>(s, lmax, true, E, k, renorm, t, srow_all + wave * e4,
+                              cand_all + row * RT_CMAX, topk_idx, topk_w, scores_out);
       }
-      if (lane == 0) flag[row] = amb ? 1 : 0;
+      if (lane == 0) flag[row] = amb;
     }
   } else {
-    if (threadIdx.x < RT_TM) flag[threadIdx.x] = (t0 + threadIdx.x < T) ? 1 : 0;
+    if (threadIdx.x < RT_TM) flag[threadIdx.x] = (t0 + threadIdx.x < T) ? RT_CMAX + 1 : 0;
   }
   __syncthreads();
   // ---- exact pass for the tokens that need it (block-uniform control flow) -------------------
   for (int row = 0; row < RT_TM; ++row) {
-    if (!flag[row]) continue;
+    const int n = flag[row];
+    if (n == 0) continue;
     const int t = t0 + row;
-    exact_partial<BF16, QE>(x + static_cast<int64_t>(t) * row16, wg, row16, E, wave, dpart);
+    const uint4* xrow = x + static_cast<int64_t>(t) * row16;
+    const int* cand = cand_all + row * RT_CMAX;
+    if (n <= RT_CMAX)
+      exact_candidates<BF16>(xrow, wg, row16, cand, n, wave, dpart);
+    else
+      exact_partial<BF16, QE>(xrow, wg, row16, E, wave, dpart);
     __syncthreads();
     if (wave == (row % RT_NW)) {
       float s[QE];
+      if (n <= RT_CMAX) {
+        // fast scores everywhere, exact (fp64 sum, one rounding) for the listed candidates
+        fast_scores(row, s);
+        for (int c = 0; c < n; ++c) {
+          const int e = cand[c];
+          double v = 0.0;
 #pragma unroll
-      for (int q = 0; q < QE; ++q) {
-        const int e = lane + MOE_WAVE * q;
-        double v = 0.0;
-        if (e < E) {
-#pragma unroll
-          for (int w = 0; w < RT_NW; ++w) v += dpart[w * E + e];
+          for (int w = 0; w < RT_NW; ++w) v += dpart[w * RT_CMAX + c];
           if (bias) v += static_cast<double>(bias[e]);
+#pragma unroll
+          for (int q = 0; q < QE; ++q)
+            if (e == lane + MOE_WAVE * q) s[q] = static_cast<float>(v);
         }
-        s[q] = static_cast<float>(v);
+      } else {
+#pragma unroll
+        for (int q = 0; q < QE; ++q) {
+          const int e = lane + MOE_WAVE * q;
+          double v = 0.0;
+          if (e < E) {
+#pragma unroll
+            for (int w = 0; w < RT_NW; ++w) v += dpart[w * E + e];
+            if (bias) v += static_cast<double>(bias[e]);
+          }
+          s[q] = static_cast<float>(v);
+        }
       }
-      route_token<QE>(s, 0.f, false, E, k, renorm, t, topk_idx, topk_w, scores_out);
+      route_token<QE>(s, 0.f, false, E, k, renorm, t, srow_all + wave * e4, nullptr, topk_idx,
+                      topk_w, scores_out);
     }
     __syncthreads();
   }
 }
 
 static size_t route_lds_bytes(int E) {
-  return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + static_cast<size_t>(RT_NW) * E * 8 +
-         RT_TM * sizeof(int);
+  const size_t e4 = (static_cast<size_t>(E) + 3) & ~static_cast<size_t>(3);
+  const size_t dn = E > RT_CMAX ? E : RT_CMAX;
+  return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 + RT_NW * e4 * 4 +
+         RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int);
 }
 
 template <bool BF16, int NT>
