@@ -389,22 +389,27 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #undef MOE_MFMA
   }
 
-  // ---- epilogue: accumulator (v, lane) holds out[row = m-sub-tile + lane%32]
-  //      [col = n-sub-tile + 8*(v/4) + 4*(lane/32) + v%4] -------------------------------------
+  // ---- epilogue.  Accumulator (v, lane) holds out[row = m-sub-tile + lane%32]
+  //      [col = n-sub-tile + 8*(v/4) + 4*(lane/32) + v%4]: 8-byte pieces scattered over 32 rows.
+  //      Each wave turns its 32-row sub-tile around in a private LDS region (row pitch = row
+  //      bytes + 8, which makes the 8-byte writes of 32 rows hit 64 different banks) and stores
+  //      whole rows, 16 bytes per lane, so the L2 sees full-line writes.
+  __builtin_amdgcn_s_barrier();                   // every wave is done with the K-loop stages
+  asm volatile("" ::: "memory");
+  constexpr int CW = NIH * 32;                    // output columns of this wave
+  constexpr int PITCH = CW * 2 + 8;               // bytes
+  constexpr int LPR = CW * 2 / 16;                // lanes that store one row
+  constexpr int RPI = 64 / LPR;                   // rows per store instruction
+  unsigned char* region = lds + wave * (32 * PITCH);
   bf16_t* out = static_cast<bf16_t*>(p.out);
-  const int row_l = wm * (BM / WM) + l32;
+  const int col0 = n0 + wn * CW;                  // first output column of this wave
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
-    const int gr = tc.m_begin + row_l + mi * 32;
-    if (gr >= tc.m_end) continue;
-    bf16_t* orow = out + static_cast<int64_t>(gr) * N;
+    if (mi < mi_valid) {                          // wave-uniform
 #pragma unroll
-    for (int ni = 0; ni < NIH; ++ni) {
-      const int cb = n0 + wn * (NIH * 32) + ni * 32 + 4 * (lane >> 5);
+      for (int ni = 0; ni < NIH; ++ni) {
 #pragma unroll
-      for (int vq = 0; vq < 4; ++vq) {
-        const int c = cb + 8 * vq;
-        if (c < N) {
+        for (int vq = 0; vq < 4; ++vq) {
           float o[4];
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
@@ -413,9 +418,25 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
             else
               o[u] = acc[ni][mi][4 * vq + u];
           }
-          *reinterpret_cast<uint2*>(orow + c) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+          const int c = ni * 32 + 8 * vq + 4 * (lane >> 5);
+          *reinterpret_cast<uint2*>(region + l32 * PITCH + c * 2) =
+              make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
         }
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
+      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 32;
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + lane / LPR;
+        const int c = (lane % LPR) * 8;           // first column of this lane's 16 bytes
+        const uint2 lo = *reinterpret_cast<const uint2*>(region + r * PITCH + c * 2);
+        const uint2 hi = *reinterpret_cast<const uint2*>(region + r * PITCH + c * 2 + 8);
+        const int gr = row_base + r;
+        if (gr < tc.m_end && col0 + c < N)
+          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) =
+              make_uint4(lo.x, lo.y, hi.x, hi.y);
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the region is reused
     }
   }
 }
