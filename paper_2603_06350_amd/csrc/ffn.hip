@@ -524,12 +524,18 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
   }
 }
 
-// Upper bounds on the number of m-tiles that need no knowledge of the counts:
-// every expert has at most floor(c/bm) full tiles (sum <= A/bm) and one remainder.
+// Upper bounds on the number of m-tiles that need no knowledge of the counts: an expert has at
+// most floor(c/bm) full tiles (sum <= A/bm) and one remainder; a main-list remainder has more
+// than SMALL_ROWS rows, so there are at most A/(SMALL_ROWS+1) main tiles in total.
 static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
   const int64_t e_cap = E < A ? E : A;
   if (mode == TILES_SMALL) return e_cap;
-  return A / bm + e_cap;
+  const int64_t ub = A / bm + e_cap;
+  if (mode == TILES_MAIN) {
+    const int64_t by_rows = A / (SMALL_ROWS + 1);
+    return ub < by_rows ? ub : by_rows;
+  }
+  return ub;
 }
 
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
@@ -545,6 +551,7 @@ static int launch_mfma(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t
   a.mode = mode;
   a.bm_main = bm_main;
   int64_t grid = max_m_tiles(A, a.E, bm_main, mode) * a.n_tiles;
+  if (grid == 0) return MOE_OK;       // no tile of this kind can exist
   grid = (grid + 7) / 8 * 8;
   if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
   hipLaunchKernelGGL((ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>), dim3(static_cast<unsigned>(grid)),
