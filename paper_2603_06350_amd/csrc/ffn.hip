@@ -17,10 +17,10 @@
 // operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
 // global -> LDS with the direct 16-byte-per-lane loads (no register staging); a wave
 // instruction fills 8 rows, and the chunk a lane fetches is XOR-swizzled by row so
-// that the 16-byte LDS reads of a 32-row MFMA operand are bank-conflict free.  The
+// that the 16-byte LDS reads of a 16-row MFMA operand are bank-conflict free.  The
 // weight fragment is the MFMA "A" operand and the activation fragment "B": a lane then
-// owns 4 consecutive output columns of one output row and stores them as one 8-byte
-// word.  v_mfma_f32_32x32x16_bf16, fp32 accumulators.
+// owns 4 consecutive output columns of one output row.  v_mfma_f32_16x16x32_bf16, fp32
+// accumulators (on this chip it sustains a higher rate than the 32x32x16 form).
 //
 // Work-group ids are remapped so that each XCD (ids are dealt round-robin to the 8
 // XCDs) walks a contiguous range of the tile list with the m-tiles of one weight
@@ -35,7 +35,7 @@
 namespace moe {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 enum TileMode { TILES_ALL = 0, TILES_MAIN = 1, TILES_SMALL = 2 };
 constexpr int SMALL_ROWS = 64;  // remainders up to this many rows go to the small-tile kernel
@@ -164,9 +164,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int NW = WM * WN;                     // waves per block
-  constexpr int KSTEPS = BK / 16;                 // MFMA k-steps per stage
-  constexpr int MI = BM / WM / 32;                // 32-row activation sub-tiles per wave
-  constexpr int NI = BROWS / WN / 32;             // 32-row weight sub-tiles per wave
+  constexpr int KSTEPS = BK / 32;                 // MFMA k-steps per stage
+  constexpr int MI = BM / WM / 16;                // 16-row activation sub-tiles per wave
+  constexpr int NI = BROWS / WN / 16;             // 16-row weight sub-tiles per wave
   constexpr int NIH = GATED ? NI / 2 : NI;        // gated: sub-tiles per weight matrix
   constexpr int STAGE = (BM + BROWS) * ROWB;      // bytes per stage
   constexpr int NLOAD = (BM + BROWS) / 8 / NW;    // direct-to-LDS instructions per wave per stage
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int NLB = 128 / 8 / NW;               // ... per 128 weight rows
   constexpr int BN_OUT = GATED ? 128 : 256;       // output columns per block tile
   static_assert(NLA * 8 * NW == BM && NLB * 8 * NW == 128 && MI >= 1 && NIH >= 1, "tile shape");
-  static_assert(KSTEPS == 4, "the pipelines below are written for four k-steps per stage");
+  static_assert(KSTEPS == 2, "the pipelines below are written for two k-steps per stage");
   extern __shared__ __align__(1024) unsigned char lds[];
 
   TileCoord tc;
@@ -190,9 +190,9 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   const bf16_t* B0 = static_cast<const bf16_t*>(p.b0) + static_cast<int64_t>(tc.e) * N * K;
   const bf16_t* B1 = GATED ? static_cast<const bf16_t*>(p.b1) + static_cast<int64_t>(tc.e) * N * K
                            : nullptr;
-  // 32-row activation sub-tiles of this wave that hold at least one valid row
+  // 16-row activation sub-tiles of this wave that hold at least one valid row
   const int rows_valid = min(tc.m_end - tc.m_begin, BM);
-  const int mi_valid = max(0, min(MI, (rows_valid - wm * (BM / WM) + 31) / 32));
+  const int mi_valid = max(0, min(MI, (rows_valid - wm * (BM / WM) + 15) / 16));
 
   // ---- global -> LDS assignment: instruction i of this wave fills row group g = i*NW + wave
   //      (8 rows x 8 chunks = 1 KiB).  Which matrix a row group belongs to depends on i alone,
@@ -219,32 +219,41 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
     }
     soff[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
   }
+  // buffer resources (raw, stride 0) based at the first row of each operand of this tile: the
+  // per-lane 32-bit offset and a scalar K offset replace 64-bit per-lane address arithmetic
+  const __amdgpu_buffer_rsrc_t rs_a =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_a), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_b0 =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_b0), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<unsigned char*>(GATED ? base_b1 : base_b0), 0, 0x7FFFFFFF, 0x00020000);
   auto issue_load = [&](int i, int kt, int stage) {
     const int g = i * NW + wave;
-    const unsigned char* base = (i < NLA) ? base_a : (!GATED || i < NLA + NLB) ? base_b0 : base_b1;
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(base + static_cast<int64_t>(kt) * ROWB + soff[i]),
-        (__attribute__((address_space(3))) void*)(lds + stage * STAGE + g * 1024), 16, 0, 0);
+    const __amdgpu_buffer_rsrc_t rs = (i < NLA) ? rs_a : (!GATED || i < NLA + NLB) ? rs_b0 : rs_b1;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        rs, (__attribute__((address_space(3))) void*)(lds + stage * STAGE + g * 1024), 16,
+        static_cast<int>(soff[i]), kt * ROWB, 0, 0);
   };
 
   // ---- LDS read addresses of the MFMA fragments ------------------------------------------------
-  const int l32 = lane & 31;
-  const int f = swz(lane);                        // sub-tile bases are multiples of 32 rows
+  // A lane holds, for row lane%16 of a 16-row sub-tile, the 8 K-elements of chunk 4*ks + lane/16.
+  const int l16 = lane & 15;
+  const int f = swz(l16);                         // sub-tile bases are multiples of 16 rows
   int koff[KSTEPS];
 #pragma unroll
-  for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = (((kk * 2 + (lane >> 5)) ^ f) << 4);
-  const int x_base = (wm * (BM / WM) + l32) * ROWB;
+  for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = (((kk * 4 + (lane >> 4)) ^ f) << 4);
+  const int x_base = (wm * (BM / WM) + l16) * ROWB;
   // first weight row of sub-tile ni relative to the wave's own first weight row
-  auto w_sub = [](int ni) { return GATED ? (ni / NIH) * 128 + (ni % NIH) * 32 : ni * 32; };
-  const int w_base = (BM + (GATED ? wn * (NIH * 32) : wn * (NI * 32)) + l32) * ROWB;
+  auto w_sub = [](int ni) { return GATED ? (ni / NIH) * 128 + (ni % NIH) * 16 : ni * 16; };
+  const int w_base = (BM + (GATED ? wn * (NIH * 16) : wn * (NI * 16)) + l16) * ROWB;
 
-  f32x16_t acc[NI][MI];
+  f32x4_t acc[NI][MI];
 #pragma unroll
   for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
+      for (int v = 0; v < 4; ++v) acc[ni][mi][v] = 0.f;
 
   // compiler-scheduled stage: used for partial tiles and by the ring pipeline
   auto compute_guarded = [&](int stage) {
@@ -255,7 +264,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
         if (mi < mi_valid)
-          xf[mi] = *reinterpret_cast<const bf16x8_t*>(sb + x_base + mi * 32 * ROWB + koff[kk]);
+          xf[mi] = *reinterpret_cast<const bf16x8_t*>(sb + x_base + mi * 16 * ROWB + koff[kk]);
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
         wf[ni] = *reinterpret_cast<const bf16x8_t*>(sb + w_base + w_sub(ni) * ROWB + koff[kk]);
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
           if (mi < mi_valid)
-            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
+            acc[ni][mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
     }
   };
 
@@ -310,11 +319,17 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
     }
   } else {
     // ---- two stages, full tile: hand-ordered pipeline --------------------------------------------
-    // Two fragment register sets (A, B) alternate over the four k-steps of a stage: the LDS reads
-    // of step kk+1 are in flight while step kk multiplies.  The global->LDS loads of the next
-    // stage are issued in two groups early in the stage so that they have most of the stage to
-    // land.  Inline asm pins the order; waits are explicit (the compiler does not see these LDS
-    // reads, so it inserts none of its own).
+    // A stage holds two k-steps (32 K-elements each).  Weight fragments live in ONE register set:
+    // as soon as the MFMAs that use w[ni] have been issued, w[ni] is re-read for the next k-step,
+    // so every LDS read has a whole k-step of MFMAs (its own wave's and the SIMD's other wave's)
+    // to land.  Activation fragments alternate between two sets.  LDS reads return in order, so
+    // "the fragment I need has landed" is s_waitcnt lgkmcnt(reads issued after it) = NI + MI - 1.
+    //
+    // The stage's one barrier sits between its two k-steps.  Before it a wave waits for its own
+    // global->LDS loads of stage kt+1 and for its last LDS reads of buffer CUR; after it, buffer
+    // CUR^1 may be read (first fragments of stage kt+1, fetched while k-step 1 multiplies) and
+    // buffer CUR may be overwritten (loads of stage kt+2, one per MFMA group).  Inline asm pins
+    // the order; the compiler does not see these LDS reads, so it inserts no waits of its own.
     int xad[2][KSTEPS], wad[2][KSTEPS];       // per stage buffer, per k-step LDS byte addresses
 #pragma unroll
     for (int st = 0; st < 2; ++st)
@@ -323,84 +338,94 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
         xad[st][kk] = st * STAGE + x_base + koff[kk];
         wad[st][kk] = st * STAGE + w_base + koff[kk];
       }
-    bf16x8_t xA[MI], wA[NI], xB[MI], wB[NI];
+    bf16x8_t xA[MI], xB[MI], wf[NI];
+    constexpr int PEND = NI + MI - 1;
+    static_assert(PEND <= 15, "lgkmcnt immediate");
 #define MOE_RD(dst, addr, off) \
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
 #define MOE_MFMA(c, w, x) \
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
-    auto read_frags = [&](bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI], int xa, int wa) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
+#define MOE_W_OFF(ni) ((GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
+    auto read_x = [&](bf16x8_t (&xf)[MI], int xa) {
 #pragma unroll
-      for (int mi = 0; mi < MI; ++mi) MOE_RD(xf[mi], xa, mi * 32 * ROWB);
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-        MOE_RD(wf[ni], wa, (GATED ? (ni / NIH) * 128 + (ni % NIH) * 32 : ni * 32) * ROWB);
-    };
-    auto mma = [&](bf16x8_t (&xf)[MI], bf16x8_t (&wf)[NI]) {
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xf[mi]);
+      for (int mi = 0; mi < MI; ++mi) MOE_RD(xf[mi], xa, mi * 16 * ROWB);
     };
     auto stage_body = [&](int kt, auto cur_c) {
       constexpr int CUR = decltype(cur_c)::value;
-      const bool more = kt + 1 < KT;
-      constexpr int G0 = (NLOAD + 1) / 2;           // load groups [0,G0) and [G0,NLOAD)
-      if (more) {
+      const bool more2 = kt + 2 < KT;               // wave-uniform
+      // k-step 0 multiplies (wf, xA) and fetches k-step 1's fragments
+      read_x(xB, xad[CUR][1]);
 #pragma unroll
-        for (int i = 0; i < G0; ++i) issue_load(i, kt + 1, CUR ^ 1);
-      }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      read_frags(xB, wB, xad[CUR][1], wad[CUR][1]);
-      mma(xA, wA);                                  // k-step 0
-      if (more) {
+      for (int ni = 0; ni < NI; ++ni) {
+        asm volatile("s_waitcnt lgkmcnt(%0)" ::"i"(PEND) : "memory");
 #pragma unroll
-        for (int i = G0; i < NLOAD; ++i) issue_load(i, kt + 1, CUR ^ 1);
+        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xA[mi]);
+        MOE_RD(wf[ni], wad[CUR][1], MOE_W_OFF(ni));
       }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      read_frags(xA, wA, xad[CUR][2], wad[CUR][2]);
-      mma(xB, wB);                                  // k-step 1
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      read_frags(xB, wB, xad[CUR][3], wad[CUR][3]);
-      mma(xA, wA);                                  // k-step 2
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      mma(xB, wB);                                  // k-step 3
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();                 // next stage landed everywhere; this one is free
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (more) read_frags(xA, wA, xad[CUR ^ 1][0], wad[CUR ^ 1][0]);
+      // k-step 1 multiplies (wf, xB): all it needs has landed.  The fragment reads below fetch
+      // the first k-step of stage kt+1; after the last stage they read stale LDS and go unused.
+      read_x(xA, xad[CUR ^ 1][0]);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xB[mi]);
+        MOE_RD(wf[ni], wad[CUR ^ 1][0], MOE_W_OFF(ni));
+        if (more2) {
+#pragma unroll
+          for (int i = 0; i < NLOAD; ++i)
+            if (i % NI == ni) issue_load(i, kt + 2, CUR);
+        }
+      }
     };
+    using T0 = std::integral_constant<int, 0>;
+    using T1 = std::integral_constant<int, 1>;
 
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) issue_load(i, 0, 0);
-    wait_vmcnt<0>();
+    if (KT > 1) {
+#pragma unroll
+      for (int i = 0; i < NLOAD; ++i) issue_load(i, 1, 1);
+      wait_vmcnt<NLOAD>();
+    } else {
+      wait_vmcnt<0>();
+    }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_frags(xA, wA, xad[0][0], wad[0][0]);
+    read_x(xA, xad[0][0]);
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) MOE_RD(wf[ni], wad[0][0], MOE_W_OFF(ni));
     int kt = 0;
     for (; kt + 1 < KT; kt += 2) {
-      stage_body(kt, std::integral_constant<int, 0>{});
-      stage_body(kt + 1, std::integral_constant<int, 1>{});
+      stage_body(kt, T0{});
+      stage_body(kt + 1, T1{});
     }
-    if (kt < KT) stage_body(kt, std::integral_constant<int, 0>{});
+    if (kt < KT) stage_body(kt, T0{});
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the unused reads of the last stage
     // the compiler's hazard handling does not see asm MFMAs: let the last results retire
     // before ordinary VALU code reads the accumulators
     asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
 #undef MOE_RD
 #undef MOE_MFMA
+#undef MOE_W_OFF
   }
 
-  // ---- epilogue.  Accumulator (v, lane) holds out[row = m-sub-tile + lane%32]
-  //      [col = n-sub-tile + 8*(v/4) + 4*(lane/32) + v%4]: 8-byte pieces scattered over 32 rows.
-  //      Each wave turns its 32-row sub-tile around in a private LDS region (row pitch = row
-  //      bytes + 8, which makes the 8-byte writes of 32 rows hit 64 different banks) and stores
-  //      whole rows, 16 bytes per lane, so the L2 sees full-line writes.
+  // ---- epilogue.  Accumulator (v, lane) holds out[row = m-sub-tile + lane%16]
+  //      [col = n-sub-tile + 4*(lane/16) + v]: 8-byte pieces scattered over 16 rows.
+  //      Each wave turns its 16-row sub-tile around in a private LDS region (row pitch = row
+  //      bytes + 32: the 32-byte runs that the four lanes of a row write land in 8 banks, and 8
+  //      consecutive rows cover all 64) and stores whole rows, 16 bytes per lane, so the L2 sees
+  //      full-line writes.
   __builtin_amdgcn_s_barrier();                   // every wave is done with the K-loop stages
   asm volatile("" ::: "memory");
-  constexpr int CW = NIH * 32;                    // output columns of this wave
-  constexpr int PITCH = CW * 2 + 8;               // bytes
+  constexpr int CW = NIH * 16;                    // output columns of this wave
+  constexpr int PITCH = CW * 2 + 32;              // bytes
   constexpr int LPR = CW * 2 / 16;                // lanes that store one row
   constexpr int RPI = 64 / LPR;                   // rows per store instruction
-  unsigned char* region = lds + wave * (32 * PITCH);
+  static_assert(16 % RPI == 0 && NW * 16 * PITCH <= NSTAGE * STAGE, "epilogue staging");
+  unsigned char* region = lds + wave * (16 * PITCH);
   bf16_t* out = static_cast<bf16_t*>(p.out);
   const int col0 = n0 + wn * CW;                  // first output column of this wave
 #pragma unroll
@@ -408,33 +433,28 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
     if (mi < mi_valid) {                          // wave-uniform
 #pragma unroll
       for (int ni = 0; ni < NIH; ++ni) {
+        float o[4];
 #pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          float o[4];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (GATED)
-              o[u] = silu_mul(acc[ni][mi][4 * vq + u], acc[GATED ? ni + NIH : ni][mi][4 * vq + u]);
-            else
-              o[u] = acc[ni][mi][4 * vq + u];
-          }
-          const int c = ni * 32 + 8 * vq + 4 * (lane >> 5);
-          *reinterpret_cast<uint2*>(region + l32 * PITCH + c * 2) =
-              make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+        for (int u = 0; u < 4; ++u) {
+          if (GATED)
+            o[u] = silu_mul(acc[ni][mi][u], acc[GATED ? ni + NIH : ni][mi][u]);
+          else
+            o[u] = acc[ni][mi][u];
         }
+        const int c = ni * 16 + 4 * (lane >> 4);
+        *reinterpret_cast<uint2*>(region + l16 * PITCH + c * 2) =
+            make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
-      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 32;
+      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 16;
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < 16 / RPI; ++it) {
         const int r = it * RPI + lane / LPR;
         const int c = (lane % LPR) * 8;           // first column of this lane's 16 bytes
-        const uint2 lo = *reinterpret_cast<const uint2*>(region + r * PITCH + c * 2);
-        const uint2 hi = *reinterpret_cast<const uint2*>(region + r * PITCH + c * 2 + 8);
+        const uint4 v = *reinterpret_cast<const uint4*>(region + r * PITCH + c * 2);
         const int gr = row_base + r;
         if (gr < tc.m_end && col0 + c < N)
-          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) =
-              make_uint4(lo.x, lo.y, hi.x, hi.y);
+          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) = v;
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the region is reused
     }
