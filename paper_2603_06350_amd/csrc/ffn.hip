@@ -28,6 +28,7 @@
 //
 // Generic kernel (fp32, or bf16 shapes whose d or F is not a multiple of 64): a plain
 // LDS-tiled FMA GEMM with fp32 accumulation.
+#include <mutex>
 #include <type_traits>
 
 #include "moe_internal.h"
@@ -591,14 +592,79 @@ static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
   return launch_status();
 }
 
-// One grouped GEMM on the MFMA path: main tiles, then the small remainders.
+static bool big_tiles(const GemmArgs& g, int64_t A) { return A / g.E >= 512; }  // mean rows per expert
+
+// Main tiles of one grouped GEMM on the MFMA path.
 template <bool GATED>
-static int mfma_gemm(const GemmArgs& g, int64_t A, hipStream_t st) {
-  const bool big = A / g.E >= 512;   // mean rows per expert
-  int rc = big ? launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st)
-               : launch_mfma<128, GATED, 2, 4, 2>(g, TILES_MAIN, 128, A, st);
-  if (rc != MOE_OK) return rc;
-  return launch_mfma<64, GATED, 2, 4, 4>(g, TILES_SMALL, big ? 256 : 128, A, st);
+static int mfma_gemm_main(const GemmArgs& g, int64_t A, hipStream_t st) {
+  return big_tiles(g, A) ? launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st)
+                         : launch_mfma<128, GATED, 2, 4, 2>(g, TILES_MAIN, 128, A, st);
+}
+
+// The small remainders of the same GEMM.
+template <bool GATED>
+static int mfma_gemm_small(const GemmArgs& g, int64_t A, hipStream_t st) {
+  return launch_mfma<64, GATED, 2, 4, 4>(g, TILES_SMALL, big_tiles(g, A) ? 256 : 128, A, st);
+}
+
+// The remainder launches stream whole weight matrices from HBM for a few rows each, while the
+// main launches are bound by the matrix pipes and the L2: run side by side they overlap.  One
+// side stream per device (default priority, created on first use, kept for the life of the
+// process) is forked from the caller's stream with an event and joined back with another, so
+// the caller sees ordinary stream semantics; the rows the two chains touch are disjoint (a
+// remainder's h rows are written and read by the side chain only).
+struct SideStream {
+  hipStream_t stream = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+  bool ready = false;
+};
+constexpr int MAX_DEVICES = 64;
+static SideStream g_side[MAX_DEVICES];
+static std::mutex g_side_mutex;   // also serialises fork ... join sequences that share the events
+
+static SideStream* side_stream_locked() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  SideStream& s = g_side[dev];
+  if (!s.ready) {
+    if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+    if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+    s.ready = true;
+  }
+  return &s;
+}
+
+// Both GEMMs (or one of them) on the MFMA path.
+static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, int64_t A,
+                    hipStream_t st) {
+  int rc = MOE_OK;
+  // Overlap pays when the main launches are long; decode-shaped calls stay on one stream.
+  const bool overlap = A / g1.E >= 128;
+  if (!overlap) {
+    if (up) {
+      if ((rc = mfma_gemm_main<true>(g1, A, st)) != MOE_OK) return rc;
+      if ((rc = mfma_gemm_small<true>(g1, A, st)) != MOE_OK) return rc;
+    }
+    if (down) {
+      if ((rc = mfma_gemm_main<false>(g2, A, st)) != MOE_OK) return rc;
+      if ((rc = mfma_gemm_small<false>(g2, A, st)) != MOE_OK) return rc;
+    }
+    return rc;
+  }
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  SideStream* side = side_stream_locked();
+  if (!side) return MOE_ERR_HIP;
+  if (hipEventRecord(side->fork, st) != hipSuccess) return MOE_ERR_HIP;
+  if (hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) return MOE_ERR_HIP;
+  // From here on the side stream must be joined back even if a launch fails.
+  if (up) rc = mfma_gemm_small<true>(g1, A, side->stream);
+  if (rc == MOE_OK && down) rc = mfma_gemm_small<false>(g2, A, side->stream);
+  if (rc == MOE_OK && up) rc = mfma_gemm_main<true>(g1, A, st);
+  if (rc == MOE_OK && down) rc = mfma_gemm_main<false>(g2, A, st);
+  if (hipEventRecord(side->join, side->stream) != hipSuccess) return MOE_ERR_HIP;
+  if (hipStreamWaitEvent(st, side->join, 0) != hipSuccess) return MOE_ERR_HIP;
+  return rc;
 }
 
 // parts: bit 0 = gated up-projection (h), bit 1 = down-projection (y_perm)
@@ -621,12 +687,7 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
     g2.n_tiles = (d + 255) / 256;
-    if (up) {
-      rc = mfma_gemm<true>(g1, A, st);
-      if (rc != MOE_OK) return rc;
-    }
-    if (down) rc = mfma_gemm<false>(g2, A, st);
-    return rc;
+    return mfma_ffn(g1, g2, up, down, A, st);
   }
   g1.n_tiles = (F + 63) / 64;
   g2.n_tiles = (d + 63) / 64;

@@ -333,3 +333,40 @@ def test_layer_end_to_end(cfg):
     torch.cuda.synchronize()
     for n, v in first.items():
         assert np.array_equal(host(getattr(buf, n)), v), f"{n} differs between two runs"
+
+
+def test_layer_replays_from_a_hip_graph():
+    """The four calls captured into one HIP graph (the grouped FFN forks its remainder launches to
+    a side stream and joins them back, which the capture must follow) replay to the eager bits.
+    Eager work and synchronisations sit between the replays; no call allocates or clears memory."""
+    cfg = si.small_config("bf16_graph", T=1400, d=128, E=2, k=2, F=256)
+    L = si.make_layer(cfg)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    bias = dev(L["gate_bias"])
+    names = ("topk_idx", "topk_w", "counts", "offsets", "dst_row", "src_assign", "x_perm", "h",
+             "y_perm", "y")
+    buf.forward(*args, gate_bias=bias)
+    torch.cuda.synchronize()
+    eager = {n: host(getattr(buf, n)).copy() for n in names}
+    ref = orc.moe_layer(L["x"], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm,
+                        L["gate_bias"])
+    assert rel_err(orc.to_f64(eager["y"]), ref["y"]) <= tol_of(cfg.dtype)
+
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        buf.forward(*args, gate_bias=bias)          # first use of this stream happens outside the capture
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=s):
+        buf.forward(*args, gate_bias=bias)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for n in names:                             # eager fills between the replays
+            getattr(buf, n).zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            assert np.array_equal(host(getattr(buf, n)), eager[n]), f"replay {rep}: {n} differs"
