@@ -2,11 +2,13 @@
 // network routes each token to its experts; the gate is a bias-free d x E linear
 // map, Sections 5 and 6.6).
 //
-// One block = 16 tokens, 8 waves.  The waves split the hidden dimension; each
-// runs v_mfma_f32_16x16x32_bf16 on its slice straight from global memory (x is
+// One block = one 16-row MFMA tile of tokens, 8 waves.  Large batches fill all 16
+// rows; small ones give a block fewer tokens (down to one, the other rows idle) so
+// that the batch still spreads over the chip.  The waves split the hidden dimension;
+// each runs v_mfma_f32_16x16x32_bf16 on its slice straight from global memory (x is
 // read exactly once from HBM, 16 B per lane; w_gate is small and stays in L2), the
 // eight partial score tiles meet in LDS and are summed in a fixed order, so the
-// scores are deterministic.  Each wave then routes two tokens by rank counting:
+// scores are deterministic.  Each wave then routes its tokens by rank counting:
 // every lane compares its scores with all E scores (broadcast LDS reads), and the
 // expert preceded by r others (larger score, or equal score and lower index) is the
 // r-th pick; the softmax weights come from the same scores.
@@ -276,11 +278,13 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
 
 // Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][max(E,RT_CMAX)] |
 //              float srow[RT_NW][E4] | int cand[RT_TM][RT_CMAX] | int flag[RT_TM]      (E4 = E rounded up to 4)
-template <bool BF16, int NT>
+// RPW = tile rows routed per wave: 2 (a full 16-token tile; compile-time so that the two tokens'
+// dependency chains interleave) or 1 (tpb <= 8 tokens per block).
+template <bool BF16, int NT, int RPW>
 __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
-    int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    float* __restrict__ scores_out) {
+    int d, int E, int k, int renorm, int tpb, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, float* __restrict__ scores_out) {
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);
@@ -292,7 +296,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   int* flag = cand_all + RT_TM * RT_CMAX;
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
-  const int t0 = blockIdx.x * RT_TM;
+  const int t0 = blockIdx.x * tpb;     // this block's tokens are tile rows [0, tpb)
   const int row16 = BF16 ? d / 8 : d / 4;
   // fp32 scores of tile row `row` from the eight partial tiles (fixed order) plus the bias;
   // returns the row's largest |logit| (before the bias)
@@ -317,7 +321,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     // ---- fast pass: partial score tiles on the matrix cores ---------------------------------
     const int r = lane & 15;   // token row of the A fragment / expert column of the B fragment
     const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
-    const int t_ld = min(t0 + r, T - 1);
+    const int t_ld = min(t0 + min(r, tpb - 1), T - 1);
     const uint4* xrow = x + static_cast<int64_t>(t_ld) * row16;
     const uint4* wrow[NT];
 #pragma unroll
@@ -374,9 +378,11 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       }
     }
     __syncthreads();
-    // ---- routing of two tokens per wave ----------------------------------------------------
-    for (int rr = 0; rr < RT_TM / RT_NW; ++rr) {
-      const int row = wave * (RT_TM / RT_NW) + rr;
+    // ---- routing: tile rows are dealt to the waves ----------------------------------------------
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int row = wave * RPW + rr;
+      if (RPW == 1 && row >= tpb) break;
       const int t = t0 + row;
       int amb = 0;
       if (t < T) {
@@ -388,11 +394,11 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       if (lane == 0) flag[row] = amb;
     }
   } else {
-    if (threadIdx.x < RT_TM) flag[threadIdx.x] = (t0 + threadIdx.x < T) ? RT_CMAX + 1 : 0;
+    if (threadIdx.x < tpb) flag[threadIdx.x] = (t0 + threadIdx.x < T) ? RT_CMAX + 1 : 0;
   }
   __syncthreads();
   // ---- exact pass for the tokens that need it (block-uniform control flow) -------------------
-  for (int row = 0; row < RT_TM; ++row) {
+  for (int row = 0; row < tpb; ++row) {
     const int n = flag[row];
     if (n == 0) continue;
     const int t = t0 + row;
@@ -445,22 +451,36 @@ static size_t route_lds_bytes(int E) {
          RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int);
 }
 
-template <bool BF16, int NT>
-static int launch_route(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                        int32_t* idx, float* w, float* scores, hipStream_t st) {
+template <bool BF16, int NT, int RPW>
+static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
+                            int32_t* idx, float* w, float* scores, int tpb, hipStream_t st) {
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<BF16, NT>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
                             static_cast<int>(route_lds_bytes(MOE_MAX_E))) != hipSuccess)
       return MOE_ERR_HIP;
     attr_set = true;
   }
-  const int grid = (s->T + RT_TM - 1) / RT_TM;
-  hipLaunchKernelGGL((route_kernel<BF16, NT>), dim3(grid), dim3(RT_THREADS), route_lds_bytes(s->E),
-                     st, static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T,
-                     s->d, s->E, s->k, s->renorm, idx, w, scores);
+  const int grid = (s->T + tpb - 1) / tpb;
+  hipLaunchKernelGGL((route_kernel<BF16, NT, RPW>), dim3(grid), dim3(RT_THREADS),
+                     route_lds_bytes(s->E), st, static_cast<const uint4*>(x),
+                     static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, s->k, s->renorm, tpb, idx,
+                     w, scores);
   return launch_status();
+}
+
+template <bool BF16, int NT>
+static int launch_route(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
+                        int32_t* idx, float* w, float* scores, hipStream_t st) {
+  // Tokens per block: a full 16-row tile when that still gives every CU a few blocks; fewer
+  // (the other tile rows idle) for small batches, where latency, not MFMA use, is what counts.
+  constexpr int GRID_TARGET = 512;
+  int tpb = RT_TM;
+  while (tpb > 1 && (s->T + tpb - 1) / tpb < GRID_TARGET) tpb >>= 1;
+  return tpb == RT_TM
+             ? launch_route_rpw<BF16, NT, 2>(s, x, wg, bias, idx, w, scores, tpb, st)
+             : launch_route_rpw<BF16, NT, 1>(s, x, wg, bias, idx, w, scores, tpb, st);
 }
 
 }  // namespace moe
