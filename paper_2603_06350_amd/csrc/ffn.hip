@@ -237,12 +237,18 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   };
 
   // ---- LDS read addresses of the MFMA fragments ------------------------------------------------
-  // A lane holds, for row lane%16 of a 16-row sub-tile, the 8 K-elements of chunk 4*ks + lane/16.
+  // A lane holds, for row lane%16 of a 16-row sub-tile, the 8 K-elements of one 16-byte chunk of
+  // the k-step's four.  Which chunk goes to which lane group is free as long as both operands
+  // agree (it only permutes the K order inside the MFMA).  The LDS serves a 16-byte read in
+  // passes of lanes {0-7, 32-39}, {8-15, 40-47}, ...: lane groups 0 and 2 therefore take chunks
+  // that differ in bit 0 (0 and 1; groups 1 and 3 take 2 and 3), which with the row swizzle
+  // makes every pass touch each bank once.
   const int l16 = lane & 15;
   const int f = swz(l16);                         // sub-tile bases are multiples of 16 rows
+  const int kgrp = ((lane >> 4) & 1) * 2 + (lane >> 5);
   int koff[KSTEPS];
 #pragma unroll
-  for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = (((kk * 4 + (lane >> 4)) ^ f) << 4);
+  for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = (((kk * 4 + kgrp) ^ f) << 4);
   const int x_base = (wm * (BM / WM) + l16) * ROWB;
   // first weight row of sub-tile ni relative to the wave's own first weight row
   auto w_sub = [](int ni) { return GATED ? (ni / NIH) * 128 + (ni % NIH) * 16 : ni * 16; };
