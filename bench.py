@@ -24,6 +24,15 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
+# HBM bytes (read, written) of one launch of the dominant call, the gated up-projection GEMM (its
+# main-tile and remainder kernels together), from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
+# runs of this script, each counter scaled by what it reads for the 1 GiB calibration copy below
+# (factors 2.000 and 1.000).  The summaries are under profiles/; a workload without one reports null.
+MEASURED_HBM_TRAFFIC = {
+    "mixtral": {"read_bytes": 2809.0e6 + 942.4e6, "written_bytes": 232.4e6 + 2.5e6,
+                "source": "profiles/mixtral_layer_all_kernels.md"},
+}
+
 CPU_SAMPLE_TOKENS = {"mixtral": 2048, "finegrained": 2048, "skew": 2048, "decode": 32, "tiny": 64}
 
 
@@ -132,15 +141,24 @@ def main():
         B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
         e[5].record(st)
     torch.cuda.synchronize()
-    per_call_ms = {n: sum(evs[it][i].elapsed_time(evs[it][i + 1]) for it in range(n_ev)) / n_ev
-                   for i, n in enumerate(names)}
+    samples = {n: sorted(evs[it][i].elapsed_time(evs[it][i + 1]) for it in range(n_ev))
+               for i, n in enumerate(names)}
+    per_call_ms = {n: sum(v) / len(v) for n, v in samples.items()}
+    per_call_ms_min = {n: v[0] for n, v in samples.items()}
+    per_call_ms_median = {n: v[len(v) // 2] for n, v in samples.items()}
 
     work = algorithmic_work(cfg)
     up_s = per_call_ms["ffn_up"] * 1e-3
     achieved = work["ffn_up_flops"] / up_s / 1e12
-    roofline = {"bound": "mfma", "kernel": "ffn_mfma_kernel<gated> (moe_grouped_ffn part 1)",
+    tr = MEASURED_HBM_TRAFFIC.get(cfg.name)
+    roofline = {"bound": "mfma",
+                "kernel": "ffn_mfma_kernel<gated>: moe_grouped_ffn part 1, main-tile launch plus the "
+                          "remainder launch that overlaps it on a side stream",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
+                "traffic": (tr["read_bytes"] + tr["written_bytes"]) if tr else None,
+                "traffic_unit": "bytes per launch (HBM read + written)",
+                "traffic_detail": tr,
                 "flops_per_launch": work["ffn_up_flops"], "avg_launch_ms": per_call_ms["ffn_up"]}
     others = {
         "ffn_down_tflops": work["ffn_down_flops"] / (per_call_ms["ffn_down"] * 1e-3) / 1e12,
@@ -150,8 +168,9 @@ def main():
         "count_and_permute_gbs": work["permute_bytes"] / (per_call_ms["count_and_permute"] * 1e-3) / 1e9,
         "combine_gbs": work["combine_bytes"] / (per_call_ms["combine"] * 1e-3) / 1e9,
         "hbm_peak_gbs": PEAK_HBM_GBS,
-        "note": "HBM-bound calls re-use the same buffers every step (cache-warm); event "
-                "timings include launch gaps",
+        "note": "every step re-uses the same buffers, but a step streams several GB of weights and "
+                "activations between two uses of a buffer, far more than the 256 MB last-level "
+                "cache holds, so the HBM-bound calls start cold; event timings include launch gaps",
     }
     out = {
         "metric": "MoE-layer tokens/sec (Mixtral shape)" if cfg.name == "mixtral"
@@ -162,7 +181,8 @@ def main():
         "dtype": "bf16" if cfg.dtype == si.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
                                f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward"},
-        "per_call_ms": per_call_ms, "roofline": roofline, "other_calls": others,
+        "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
+        "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, L, CPU_SAMPLE_TOKENS.get(cfg.name, min(cfg.T, 256)))
