@@ -39,5 +39,26 @@ def build(verbose: bool = False, extra=(), out: str = LIB) -> str:
     return out
 
 
+MICROBENCH = ["mfma_rate", "l2_to_lds_stream"]
+
+
+def build_microbench(verbose: bool = False) -> list:
+    """The stand-alone micro-benchmarks under csrc/microbench (context for the rooflines)."""
+    outs = []
+    for name in MICROBENCH:
+        src = os.path.join(CSRC, "microbench", name + ".hip")
+        out = os.path.join(CSRC, "microbench", name + ".exe")
+        cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", src, "-o", out]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stderr)
+        outs.append(out)
+    return outs
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_microbench(verbose=True))
