@@ -174,3 +174,15 @@ def expert_weights(cfg: LayerConfig, e: int):
     return (_normal((cfg.seed, 2, e), (cfg.F, cfg.d), w_std, cfg.dtype),
             _normal((cfg.seed, 3, e), (cfg.F, cfg.d), w_std, cfg.dtype),
             _normal((cfg.seed, 4, e), (cfg.d, cfg.F), w_std, cfg.dtype))
+
+
+def zipf_loads(E: int, total: int, alpha: float, seed: int) -> np.ndarray:
+    """Synthetic per-expert token counts of one layer (int64 [E], summing to `total`): a multinomial
+    draw with expert probabilities proportional to rank^-alpha, ranks shuffled over the expert
+    indices.  Stands in for the skewed expert loads of the paper's traces (its Section 3.1
+    characterisation: a few stragglers carry most tokens)."""
+    rng = np.random.default_rng([int(seed), 77, int(E)])
+    p = np.arange(1, E + 1, dtype=np.float64) ** (-float(alpha))
+    p /= p.sum()
+    rng.shuffle(p)
+    return rng.multinomial(int(total), p).astype(np.int64)
