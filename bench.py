@@ -73,6 +73,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mixtral")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-consumers", action="store_true",
+                    help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this build has no sharded path (one process, one "
@@ -147,6 +149,69 @@ def main():
     per_call_ms_min = {n: v[0] for n, v in samples.items()}
     per_call_ms_median = {n: v[len(v) // 2] for n, v in samples.items()}
 
+    # Consumers of the load statistic (not part of the step): Algorithm 1 on the layer's own counts,
+    # and a speculative predictor pass (a second gate matrix on the same x) on a side stream.
+    consumers = None
+    if not args.no_consumers:
+        pred = layer.LoadPredictor(cfg.T, cfg.d, cfg.E, cfg.k, cfg.dtype, cfg.renorm,
+                                   max_extra_replicas=cfg.E)
+        w_pred = layer.to_device(si.make_layer(
+            si.small_config("predictor_gate", T=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, F=cfg.F,
+                            dtype=cfg.dtype, renorm=cfg.renorm, seed=cfg.seed + 1),
+            parts=("w_gate",))["w_gate"])
+        rep = torch.empty((cfg.E,), dtype=torch.int32, device="cuda")
+        cvs = torch.empty((2,), dtype=torch.float64, device="cuda")
+        n_it = 200
+
+        def timed(fn):
+            for _ in range(5):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record(st)
+            for _ in range(n_it):
+                fn()
+            e1.record(st)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n_it * 1e3
+
+        scale_us = timed(lambda: (
+            B.moe_scale_replicas(cfg.E, buf.counts, 1, cfg.E, 0.2, rep, cvs, st),
+            B.moe_replica_segments(cfg.E, buf.offsets, rep, pred.max_segments, pred.seg_offsets,
+                                   pred.seg_expert, pred.n_segments, st)))
+        cv_before, cv_after = (float(v) for v in cvs.cpu())
+        extra = int(rep.sum().item()) - cfg.E
+        pred_us = timed(lambda: pred.enqueue(x, w_pred, None, 0.2, st))
+        side = torch.cuda.Stream()
+        fork = torch.cuda.Event()
+
+        def step_with_predictor():
+            fork.record(st)
+            side.wait_event(fork)
+            pred.enqueue(x, w_pred, None, 0.2, side)
+            step()
+            st.wait_stream(side)
+
+        for _ in range(3):
+            step_with_predictor()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step_with_predictor()
+        torch.cuda.synchronize()
+        ms_with = (time.perf_counter() - t1) * 1e3 / args.steps
+        consumers = {
+            "scale_and_segments_us": scale_us,
+            "scaling": {"M_e": 1, "M_cap": cfg.E, "V": 0.2, "cv_before": cv_before,
+                        "cv_after": cv_after, "extra_replicas": extra},
+            "predictor_pass_us": pred_us,
+            "predictor_pass": "moe_route with a second seeded gate matrix + counts + Algorithm 1 + "
+                              "replica segments, alone on the stream",
+            "ms_per_step_with_predictor_on_side_stream": ms_with,
+            "added_ms_per_step": ms_with - ms_per_step,
+            "paper_prediction_delay_ms": "< 0.2 per layer (Section 6.6, other hardware)",
+        }
+
     work = algorithmic_work(cfg)
     up_s = per_call_ms["ffn_up"] * 1e-3
     achieved = work["ffn_up_flops"] / up_s / 1e12
@@ -184,6 +249,8 @@ def main():
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
         "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,
     }
+    if consumers is not None:
+        out["load_consumers"] = consumers
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, L, CPU_SAMPLE_TOKENS.get(cfg.name, min(cfg.T, 256)))
     print(json.dumps(out))

@@ -127,6 +127,44 @@ int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm, const int
 int moe_combine(const moe_shape_t* shape, const void* y_perm, const int32_t* dst_row,
                 const float* topk_w, void* y, void* hip_stream);
 
+/*
+ * Expert Scaling (Algorithm 1, Section 4.2): how many replicas each expert of a layer gets.
+ * `loads` [E] are the layer's (predicted or measured) per-expert token counts, e.g. the
+ * `counts` of moe_count_and_permute; negative entries count as 0.  Every expert starts with
+ * one replica and no extra memory allocated.  While one more replica still fits
+ * (allocated + expert_mem <= mem_cap; expert_mem = M_e > 0 and mem_cap = M_cap >= 0 in the same
+ * unit) and the coefficient of variation of the per-replica loads exceeds `cv_threshold`
+ * (V), the expert whose replicas carry the largest load W_e / R_e gets one more replica
+ * (equal loads: the lowest index; an expert with no load is never split).  CV is the
+ * population standard deviation over the mean of the multiset that holds W_e / R_e once per
+ * replica, computed in fp64; 0 for an all-zero layer.
+ *   replicas [E] int32   R_e >= 1
+ *   cv_out   [2] double  optional (may be NULL): CV before the first step (= CV of `loads`
+ *                        themselves) and CV of the returned replica counts
+ * E <= 256; mem_cap / expert_mem <= MOE_MAX_EXTRA_REPLICAS (else MOE_ERR_UNSUPPORTED).
+ * One small launch on `hip_stream`; nothing is read back to the host.
+ */
+#define MOE_MAX_EXTRA_REPLICAS 65536
+int moe_scale_replicas(int32_t E, const int32_t* loads, int64_t expert_mem, int64_t mem_cap,
+                       double cv_threshold, int32_t* replicas, double* cv_out, void* hip_stream);
+
+/*
+ * Even split of every expert's rows over its replicas (Section 3.3: an expert's load is
+ * divided evenly among its replicas).  Expert e owns rows [offsets[e], offsets[e+1]) of the
+ * permuted order; replica r of its R_e = replicas[e] gets the rows
+ *   [offsets[e] + floor(c*r/R_e), offsets[e] + floor(c*(r+1)/R_e)),   c = offsets[e+1]-offsets[e],
+ * so piece sizes differ by at most one row.  Segments are listed expert-major.
+ *   n_segments  [1] int32            S = sum_e R_e
+ *   seg_offsets [max_segments+1]     seg_offsets[0] = offsets[0]; segment s covers rows
+ *                                    [seg_offsets[s], seg_offsets[s+1])
+ *   seg_expert  [max_segments]       the expert of segment s
+ * Only the first min(S, max_segments) segments are written; a caller that cannot bound S
+ * checks n_segments afterwards.  E <= 256.  One small launch; no host synchronisation.
+ */
+int moe_replica_segments(int32_t E, const int32_t* offsets, const int32_t* replicas,
+                         int32_t max_segments, int32_t* seg_offsets, int32_t* seg_expert,
+                         int32_t* n_segments, void* hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char* moe_strerror(int code);
 

@@ -18,7 +18,9 @@ _LIB_PATH = os.environ.get("MOE_GFX950_LIB") or os.path.join(
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",
-           "moe_grouped_ffn_part", "moe_combine", "moe_strerror")
+           "moe_grouped_ffn_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
+           "moe_strerror")
+MOE_MAX_EXTRA_REPLICAS = 65536
 
 
 class MoeShape(ctypes.Structure):
@@ -54,6 +56,10 @@ def load():
     lib.moe_grouped_ffn.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, vp]
     lib.moe_grouped_ffn_part.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.moe_combine.argtypes = [shp, vp, i32p, f32p, vp, vp]
+    lib.moe_scale_replicas.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int64,
+                                       ctypes.c_double, i32p, vp, vp]
+    lib.moe_replica_segments.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p,
+                                         i32p, vp]
     lib.moe_strerror.argtypes = [ctypes.c_int]
     lib.moe_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -129,3 +135,18 @@ def moe_grouped_ffn_part(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, st
 def moe_combine(shape, y_perm, dst_row, topk_w, y, stream=None):
     _check("moe_combine", load().moe_combine(ctypes.byref(shape), _ptr(y_perm), _ptr(dst_row),
                                              _ptr(topk_w), _ptr(y), _stream(stream)))
+
+
+def moe_scale_replicas(E, loads, expert_mem, mem_cap, cv_threshold, replicas, cv_out=None, stream=None):
+    _check("moe_scale_replicas",
+           load().moe_scale_replicas(int(E), _ptr(loads), int(expert_mem), int(mem_cap),
+                                     float(cv_threshold), _ptr(replicas), _ptr(cv_out),
+                                     _stream(stream)))
+
+
+def moe_replica_segments(E, offsets, replicas, max_segments, seg_offsets, seg_expert, n_segments,
+                         stream=None):
+    _check("moe_replica_segments",
+           load().moe_replica_segments(int(E), _ptr(offsets), _ptr(replicas), int(max_segments),
+                                       _ptr(seg_offsets), _ptr(seg_expert), _ptr(n_segments),
+                                       _stream(stream)))

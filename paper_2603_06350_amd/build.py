@@ -12,7 +12,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmoe_gfx950.so")
-SOURCES = ["route.hip", "dispatch.hip", "ffn.hip", "combine.hip", "status.hip"]
+SOURCES = ["route.hip", "dispatch.hip", "ffn.hip", "combine.hip", "scaler.hip", "status.hip"]
 
 
 def hipcc() -> str:

@@ -60,3 +60,49 @@ class MoeBuffers:
         B.moe_grouped_ffn(self.shape, self.x_perm, self.offsets, w1, w3, w2, self.h, self.y_perm, s)
         B.moe_combine(self.shape, self.y_perm, self.dst_row, self.topk_w, self.y, s)
         return self.y
+
+
+class LoadPredictor:
+    """Speculative expert-load prediction for a later layer (paper, Section 4.1): the hidden states
+    that enter layer l go through the gate of layer l+d (a replica of that gate, fine-tuned or
+    not) to estimate that layer's per-expert token counts ahead of time, and Algorithm 1 turns the
+    estimate into replica counts.  Everything is enqueued on one stream, meant to be a side stream
+    next to the layer's own forward (Section 5: predictors run asynchronously on dedicated
+    streams); nothing is read back to the host.
+
+    enqueue() = moe_route (predictor weights) -> moe_count_and_permute without the row gather ->
+    moe_scale_replicas -> moe_replica_segments.  Outputs stay in `counts`, `offsets`, `replicas`,
+    `cv` ([before, after]), `seg_offsets`, `seg_expert`, `n_segments`."""
+
+    def __init__(self, T, d, E, k, dtype, renorm, max_extra_replicas, device="cuda"):
+        # F does not enter any of the calls used here; 8 keeps the shape valid for both dtypes
+        self.shape = B.make_shape(T, d, E, k, 8, dtype, renorm)
+        self.E = E
+        self.max_extra = int(max_extra_replicas)
+        A = T * k
+        kw = dict(device=device)
+        self.topk_idx = torch.empty((T, k), dtype=torch.int32, **kw)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, **kw)
+        self.counts = torch.empty((E,), dtype=torch.int32, **kw)
+        self.offsets = torch.empty((E + 1,), dtype=torch.int32, **kw)
+        self.dst_row = torch.empty((A,), dtype=torch.int32, **kw)
+        self.src_assign = torch.empty((A,), dtype=torch.int32, **kw)
+        self.ws_bytes = B.moe_workspace_bytes(self.shape)
+        self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, **kw)
+        self.replicas = torch.empty((E,), dtype=torch.int32, **kw)
+        self.cv = torch.empty((2,), dtype=torch.float64, **kw)
+        self.max_segments = E + self.max_extra
+        self.seg_offsets = torch.empty((self.max_segments + 1,), dtype=torch.int32, **kw)
+        self.seg_expert = torch.empty((self.max_segments,), dtype=torch.int32, **kw)
+        self.n_segments = torch.empty((1,), dtype=torch.int32, **kw)
+
+    def enqueue(self, x, w_pred, gate_bias=None, cv_threshold=0.2, stream=None):
+        s = torch.cuda.current_stream() if stream is None else stream
+        B.moe_route(self.shape, x, w_pred, gate_bias, self.topk_idx, self.topk_w, None, s)
+        B.moe_count_and_permute(self.shape, None, self.topk_idx, self.counts, self.offsets,
+                                self.dst_row, self.src_assign, None, self.workspace, self.ws_bytes, s)
+        # memory in units of one expert: the cap is the number of additional replicas
+        B.moe_scale_replicas(self.E, self.counts, 1, self.max_extra, cv_threshold, self.replicas,
+                             self.cv, s)
+        B.moe_replica_segments(self.E, self.offsets, self.replicas, self.max_segments,
+                               self.seg_offsets, self.seg_expert, self.n_segments, s)

@@ -102,3 +102,26 @@ def test_product_package_does_not_import_the_oracle(repo_root):
     for fn in os.listdir(os.path.join(repo_root, "oracle")):
         if fn.endswith(".py"):
             assert "paper_2603_06350_amd" not in open(os.path.join(repo_root, "oracle", fn)).read()
+
+
+def test_scaler_calls_validate_on_the_host(lib):
+    one = 0x1000   # never dereferenced: every case below fails validation first
+    cases = [
+        (lambda: B.moe_scale_replicas(0, one, 1, 4, 0.2, one), -1),          # E < 1
+        (lambda: B.moe_scale_replicas(8, None, 1, 4, 0.2, one), -1),         # no loads
+        (lambda: B.moe_scale_replicas(8, one, 1, 4, 0.2, None), -1),         # no output
+        (lambda: B.moe_scale_replicas(8, one, 0, 4, 0.2, one), -1),          # M_e < 1
+        (lambda: B.moe_scale_replicas(8, one, 1, -1, 0.2, one), -1),         # M_cap < 0
+        (lambda: B.moe_scale_replicas(8, one, 1, 4, float("nan"), one), -1),
+        (lambda: B.moe_scale_replicas(300, one, 1, 4, 0.2, one), -2),        # E > 256
+        (lambda: B.moe_scale_replicas(8, one, 1, B.MOE_MAX_EXTRA_REPLICAS + 1, 0.2, one), -2),
+        (lambda: B.moe_replica_segments(0, one, one, 16, one, one, one), -1),
+        (lambda: B.moe_replica_segments(8, None, one, 16, one, one, one), -1),
+        (lambda: B.moe_replica_segments(8, one, one, -1, one, one, one), -1),
+        (lambda: B.moe_replica_segments(8, one, one, 16, one, one, None), -1),
+        (lambda: B.moe_replica_segments(300, one, one, 16, one, one, one), -2),
+    ]
+    for call, code in cases:
+        with pytest.raises(B.MoeError) as ei:
+            call()
+        assert ei.value.code == code
