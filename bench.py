@@ -2,8 +2,9 @@
 """MoE-layer forward benchmark on one MI355X.
 
 A step is one pass of the whole hot path (moe_route -> moe_count_and_permute ->
-moe_grouped_ffn -> moe_combine) over one seeded synthetic batch that is already
-resident in HBM.  Prints ONE JSON line: whole-layer tokens/s, per-call times, the
+moe_grouped_ffn_gather -> moe_combine; with --materialize-x-perm the four-call form
+with moe_grouped_ffn on a written x_perm) over one seeded synthetic batch that is
+already resident in HBM.  Prints ONE JSON line: whole-layer tokens/s, per-call times, the
 roofline of the dominant kernel (the gated up-projection GEMM of the grouped FFN)
 and the CPU oracle timed on the host cores on a bounded sample of the same batch.
 
@@ -43,6 +44,7 @@ def algorithmic_work(cfg):
     return {
         "route_bytes": T * d * b + E * d * b + 8 * A,
         "permute_bytes": T * d * b + A * d * b + 4 * A + 8 * A + 8 * E,
+        "permute_maps_only_bytes": 4 * A + 8 * A + 8 * E,
         "ffn_up_flops": 4 * d * F * A,        # two d x F products per routed row
         "ffn_down_flops": 2 * d * F * A,
         "combine_bytes": A * d * b + T * d * b + 8 * A,
@@ -73,6 +75,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mixtral")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--materialize-x-perm", action="store_true",
+                    help="write the permuted activations and run the FFN on them (the four-call form); "
+                         "default: the up-projection reads x through the permutation map")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -98,11 +103,28 @@ def main():
     st = torch.cuda.current_stream()
     sh = buf.shape
 
+    fused = not args.materialize_x_perm
+
+    def call_permute():
+        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
+                                buf.src_assign, None if fused else buf.x_perm, buf.workspace,
+                                buf.ws_bytes, st)
+
+    def call_ffn(part=None):
+        if fused and part is None:
+            B.moe_grouped_ffn_gather(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+        elif fused:
+            B.moe_grouped_ffn_gather_part(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h,
+                                          buf.y_perm, part, st)
+        elif part is None:
+            B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+        else:
+            B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, part, st)
+
     def step():
         B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
-        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
-                                buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
-        B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+        call_permute()
+        call_ffn()
         B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
 
     # One plain copy kernel of known size (1 GiB read + 1 GiB written) so that a profiler's
@@ -133,12 +155,11 @@ def main():
         e[0].record(st)
         B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
         e[1].record(st)
-        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
-                                buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
+        call_permute()
         e[2].record(st)
-        B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 1, st)
+        call_ffn(1)
         e[3].record(st)
-        B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 2, st)
+        call_ffn(2)
         e[4].record(st)
         B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
         e[5].record(st)
@@ -217,8 +238,9 @@ def main():
     achieved = work["ffn_up_flops"] / up_s / 1e12
     tr = MEASURED_HBM_TRAFFIC.get(cfg.name)
     roofline = {"bound": "mfma",
-                "kernel": "ffn_mfma_kernel<gated>: moe_grouped_ffn part 1, main-tile launch plus the "
-                          "remainder launch that overlaps it on a side stream",
+                "kernel": "ffn_mfma_kernel<gated>: part 1 of " +
+                          ("moe_grouped_ffn_gather" if fused else "moe_grouped_ffn") +
+                          ", main-tile launch plus the remainder launch that overlaps it on a side stream",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
                 "traffic": (tr["read_bytes"] + tr["written_bytes"]) if tr else None,
@@ -230,7 +252,10 @@ def main():
         "ffn_total_frac_of_mfma_peak": (work["ffn_up_flops"] + work["ffn_down_flops"]) /
         ((per_call_ms["ffn_up"] + per_call_ms["ffn_down"]) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
         "route_gbs": work["route_bytes"] / (per_call_ms["route"] * 1e-3) / 1e9,
-        "count_and_permute_gbs": work["permute_bytes"] / (per_call_ms["count_and_permute"] * 1e-3) / 1e9,
+        "count_and_permute_gbs": (work["permute_maps_only_bytes"] if fused else work["permute_bytes"]) /
+        (per_call_ms["count_and_permute"] * 1e-3) / 1e9,
+        "count_and_permute_form": "maps only: the up-projection reads x through src_assign (latency-bound "
+                                  "integer work, no HBM roofline claim)" if fused else "maps + x_perm rows",
         "combine_gbs": work["combine_bytes"] / (per_call_ms["combine"] * 1e-3) / 1e9,
         "hbm_peak_gbs": PEAK_HBM_GBS,
         "note": "every step re-uses the same buffers, but a step streams several GB of weights and "
@@ -245,7 +270,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == si.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
-                               f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward"},
+                               f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward",
+                   "ffn_input": "x through the permutation map (moe_grouped_ffn_gather)" if fused
+                   else "materialised x_perm (moe_grouped_ffn)"},
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
         "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,
     }

@@ -120,6 +120,25 @@ int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm, const int
                          int part, void* hip_stream);
 
 /*
+ * moe_grouped_ffn without the permuted copy of the activations: the up-projection reads the
+ * rows of x [T,d] directly, row r of the permuted order being x[src_assign[r] / k] (the
+ * `src_assign` map of moe_count_and_permute, which may then be called with x_perm = NULL).
+ * Same h and y_perm, bit for bit, as moe_grouped_ffn on the x_perm that call would have
+ * written; the T*k*d*b bytes of x_perm are neither written nor read.  Entries of
+ * src_assign outside [0, T*k) give unspecified values in their rows (never out-of-bounds
+ * accesses).  T*d*b must be below 2^31 (else MOE_ERR_UNSUPPORTED).
+ */
+int moe_grouped_ffn_gather(const moe_shape_t* shape, const void* x, const int32_t* src_assign,
+                           const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                           void* h, void* y_perm, void* hip_stream);
+
+/* One half of moe_grouped_ffn_gather, as moe_grouped_ffn_part is of moe_grouped_ffn
+ * (part 1 reads x through src_assign and writes h; part 2 reads h and writes y_perm). */
+int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x, const int32_t* src_assign,
+                                const int32_t* offsets, const void* w1, const void* w3,
+                                const void* w2, void* h, void* y_perm, int part, void* hip_stream);
+
+/*
  * Weighted combine (Section 2.2: the gather that collects and reorders expert
  * outputs):   y[t,:] = sum_{j<k} topk_w[t,j] * y_perm[dst_row[t*k+j], :]
  * summed in fp32 in ascending j, stored once in `dtype`.  y [T,d].

@@ -18,7 +18,8 @@ _LIB_PATH = os.environ.get("MOE_GFX950_LIB") or os.path.join(
 _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",
-           "moe_grouped_ffn_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
+           "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
+           "moe_grouped_ffn_gather_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
            "moe_strerror")
 MOE_MAX_EXTRA_REPLICAS = 65536
 
@@ -55,6 +56,9 @@ def load():
                                           ctypes.c_size_t, vp]
     lib.moe_grouped_ffn.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, vp]
     lib.moe_grouped_ffn_part.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp]
+    lib.moe_grouped_ffn_gather.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp]
+    lib.moe_grouped_ffn_gather_part.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp,
+                                                ctypes.c_int, vp]
     lib.moe_combine.argtypes = [shp, vp, i32p, f32p, vp, vp]
     lib.moe_scale_replicas.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int64,
                                        ctypes.c_double, i32p, vp, vp]
@@ -130,6 +134,21 @@ def moe_grouped_ffn_part(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, st
            load().moe_grouped_ffn_part(ctypes.byref(shape), _ptr(x_perm), _ptr(offsets), _ptr(w1),
                                        _ptr(w3), _ptr(w2), _ptr(h), _ptr(y_perm), int(part),
                                        _stream(stream)))
+
+
+def moe_grouped_ffn_gather(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, stream=None):
+    _check("moe_grouped_ffn_gather",
+           load().moe_grouped_ffn_gather(ctypes.byref(shape), _ptr(x), _ptr(src_assign),
+                                         _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(h),
+                                         _ptr(y_perm), _stream(stream)))
+
+
+def moe_grouped_ffn_gather_part(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, part,
+                                stream=None):
+    _check("moe_grouped_ffn_gather_part",
+           load().moe_grouped_ffn_gather_part(ctypes.byref(shape), _ptr(x), _ptr(src_assign),
+                                              _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(h),
+                                              _ptr(y_perm), int(part), _stream(stream)))
 
 
 def moe_combine(shape, y_perm, dst_row, topk_w, y, stream=None):

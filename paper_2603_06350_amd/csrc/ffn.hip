@@ -52,7 +52,19 @@ struct GemmArgs {
   int rows;         // T*k; row ranges read from `offsets` are clamped to it
   int mode;         // TileMode
   int bm_main;      // rows of a main tile (also the unit remainders are taken against)
+  // Gathered activations: row r of the GEMM is row src_assign[r] / k_div of `a` (the token that
+  // assignment r belongs to) instead of row r itself.  nullptr = `a` is already permuted.
+  const int32_t* src_assign;
+  int k_div;
+  int a_rows;       // rows of `a` (gathered row numbers are clamped to it)
 };
+
+// Row of `a` that holds GEMM row r.
+__device__ __forceinline__ int a_row_of(const GemmArgs& p, int r) {
+  if (!p.src_assign) return r;
+  const int t = p.src_assign[r] / p.k_div;
+  return min(max(t, 0), p.a_rows - 1);
+}
 
 struct TileCoord {
   int e, m_begin, m_end, n_tile;
@@ -199,8 +211,9 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   //      (8 rows x 8 chunks = 1 KiB).  Which matrix a row group belongs to depends on i alone,
   //      so each instruction has a uniform 64-bit base and a 32-bit per-lane offset.  Rows past
   //      the end of the segment (or of the weight matrix) re-read the last valid row.
-  const unsigned char* base_a =
-      reinterpret_cast<const unsigned char*>(A + static_cast<int64_t>(tc.m_begin) * K);
+  const bool gathered = p.src_assign != nullptr;  // uniform
+  const unsigned char* base_a = reinterpret_cast<const unsigned char*>(
+      gathered ? A : A + static_cast<int64_t>(tc.m_begin) * K);
   const unsigned char* base_b0 =
       reinterpret_cast<const unsigned char*>(B0 + static_cast<int64_t>(n0) * K);
   const unsigned char* base_b1 =
@@ -214,6 +227,8 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
     int r;                                        // row relative to the instruction's base
     if (i < NLA) {
       r = min(row, rows_valid - 1);
+      // gathered: the offset is taken from the start of `a` (the host checks that it fits 31 bits)
+      if (gathered) r = a_row_of(p, tc.m_begin + r);
     } else {
       const int br = row - BM;
       r = GATED ? min(br & 127, N - 1 - n0) : min(br, N - 1 - n0);
@@ -499,7 +514,7 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 4; ++j) acc[s][i][j] = 0.f;
-  const int a_row = min(tc.m_begin + lr, tc.m_end - 1);
+  const int a_row = a_row_of(p, min(tc.m_begin + lr, tc.m_end - 1));
   const int b_row = min(n0 + lr, N - 1);
   for (int k0 = 0; k0 < K; k0 += TK) {
 #pragma unroll
@@ -674,21 +689,28 @@ static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, 
 }
 
 // parts: bit 0 = gated up-projection (h), bit 1 = down-projection (y_perm)
-static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
-                            const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
-                            int parts, void* hip_stream) {
+// x_perm [T*k, d] with src_assign == nullptr, or x [T, d] with the src_assign map of the dispatch
+static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* src_assign,
+                            const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                            void* h, void* y_perm, int parts, void* hip_stream) {
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
   if (!x_perm || !offsets || !w1 || !w3 || !w2 || !h || !y_perm) return MOE_ERR_INVALID_ARG;
+  // gathered rows are addressed with a 32-bit byte offset from the start of x
+  if (src_assign && static_cast<int64_t>(shape->T) * shape->d * elem_bytes(shape->dtype) >=
+                        (int64_t(1) << 31))
+    return MOE_ERR_UNSUPPORTED;
   if (!aligned16(x_perm) || !aligned16(w1) || !aligned16(w3) || !aligned16(w2) || !aligned16(h) ||
       !aligned16(y_perm))
     return MOE_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t A = static_cast<int64_t>(shape->T) * shape->k;
   const int d = shape->d, F = shape->F, E = shape->E;
-  GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_ALL, 64};
-  GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_ALL, 64};
+  GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_ALL, 64,
+              src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A)};
+  GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_ALL, 64,
+              nullptr, 1, static_cast<int>(A)};
   const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
@@ -718,7 +740,26 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
 extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
                                const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
                                void* hip_stream) {
-  return moe::grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
+  return moe::grouped_ffn_impl(shape, x_perm, nullptr, offsets, w1, w3, w2, h, y_perm, 3,
+                               hip_stream);
+}
+
+extern "C" int moe_grouped_ffn_gather(const moe_shape_t* shape, const void* x,
+                                      const int32_t* src_assign, const int32_t* offsets,
+                                      const void* w1, const void* w3, const void* w2, void* h,
+                                      void* y_perm, void* hip_stream) {
+  if (!src_assign) return MOE_ERR_INVALID_ARG;
+  return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
+}
+
+extern "C" int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x,
+                                           const int32_t* src_assign, const int32_t* offsets,
+                                           const void* w1, const void* w3, const void* w2, void* h,
+                                           void* y_perm, int part, void* hip_stream) {
+  if (part != 1 && part != 2) return MOE_ERR_INVALID_ARG;
+  if (!src_assign) return MOE_ERR_INVALID_ARG;
+  return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, part,
+                               hip_stream);
 }
 
 extern "C" int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm,
@@ -726,5 +767,6 @@ extern "C" int moe_grouped_ffn_part(const moe_shape_t* shape, const void* x_perm
                                     const void* w2, void* h, void* y_perm, int part,
                                     void* hip_stream) {
   if (part != 1 && part != 2) return MOE_ERR_INVALID_ARG;
-  return moe::grouped_ffn_impl(shape, x_perm, offsets, w1, w3, w2, h, y_perm, part, hip_stream);
+  return moe::grouped_ffn_impl(shape, x_perm, nullptr, offsets, w1, w3, w2, h, y_perm, part,
+                               hip_stream);
 }

@@ -49,15 +49,23 @@ class MoeBuffers:
         self.ws_bytes = B.moe_workspace_bytes(self.shape)
         self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, **kw)
 
-    def forward(self, x, w_gate, w1, w3, w2, gate_bias=None, stream=None, export_scores=False):
-        """The whole hot path: route -> count+permute -> grouped FFN -> combine."""
+    def forward(self, x, w_gate, w1, w3, w2, gate_bias=None, stream=None, export_scores=False,
+                gather_in_ffn=False):
+        """The whole hot path: route -> count+permute -> grouped FFN -> combine.
+        gather_in_ffn: the up-projection reads x through the permutation map and x_perm is not
+        materialised (same results, bit for bit)."""
         s = torch.cuda.current_stream() if stream is None else stream
         B.moe_route(self.shape, x, w_gate, gate_bias, self.topk_idx, self.topk_w,
                     self.scores if export_scores else None, s)
         B.moe_count_and_permute(self.shape, x, self.topk_idx, self.counts, self.offsets,
-                                self.dst_row, self.src_assign, self.x_perm, self.workspace,
-                                self.ws_bytes, s)
-        B.moe_grouped_ffn(self.shape, self.x_perm, self.offsets, w1, w3, w2, self.h, self.y_perm, s)
+                                self.dst_row, self.src_assign, None if gather_in_ffn else self.x_perm,
+                                self.workspace, self.ws_bytes, s)
+        if gather_in_ffn:
+            B.moe_grouped_ffn_gather(self.shape, x, self.src_assign, self.offsets, w1, w3, w2,
+                                     self.h, self.y_perm, s)
+        else:
+            B.moe_grouped_ffn(self.shape, self.x_perm, self.offsets, w1, w3, w2, self.h,
+                              self.y_perm, s)
         B.moe_combine(self.shape, self.y_perm, self.dst_row, self.topk_w, self.y, s)
         return self.y
 

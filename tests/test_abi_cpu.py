@@ -71,6 +71,7 @@ def test_shape_validation_happens_before_any_launch(lib):
                  lambda: B.moe_count_and_permute(ok, None, None, None, None, None, None, None,
                                                  None, 0),
                  lambda: B.moe_grouped_ffn(ok, None, None, None, None, None, None, None),
+                 lambda: B.moe_grouped_ffn_gather(ok, None, None, None, None, None, None, None, None),
                  lambda: B.moe_combine(ok, None, None, None, None)):
         with pytest.raises(B.MoeError) as ei:
             call()

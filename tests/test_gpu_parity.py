@@ -370,3 +370,44 @@ def test_layer_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         for n in names:
             assert np.array_equal(host(getattr(buf, n)), eager[n]), f"replay {rep}: {n} differs"
+
+
+@pytest.mark.parametrize("cfg", LAYER_CASES, ids=lambda c: c.name)
+def test_ffn_reading_x_through_the_permutation_gives_the_same_bits(cfg):
+    """moe_grouped_ffn_gather (no x_perm) against moe_grouped_ffn on the materialised x_perm."""
+    L = si.make_layer(cfg)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    bias = dev(L["gate_bias"])
+    buf.forward(*args, gate_bias=bias)
+    torch.cuda.synchronize()
+    want = {n: host(getattr(buf, n)).copy() for n in ("src_assign", "h", "y_perm", "y")}
+    for n in ("x_perm", "h", "y_perm", "y"):
+        getattr(buf, n).zero_()
+    buf.forward(*args, gate_bias=bias, gather_in_ffn=True)
+    torch.cuda.synchronize()
+    for n, v in want.items():
+        assert np.array_equal(host(getattr(buf, n)), v), n
+    assert not host(buf.x_perm).any()                   # x_perm was not touched
+    ref = orc.moe_layer(L["x"], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm,
+                        L["gate_bias"])
+    assert rel_err(orc.to_f64(host(buf.y)), ref["y"]) <= tol_of(cfg.dtype)
+
+
+def test_ffn_gather_rejects_missing_map_and_survives_bad_entries():
+    cfg = si.small_config("gather_bad", T=200, d=128, E=4, k=2, F=128)
+    L = si.make_layer(cfg)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    buf.forward(*args, gather_in_ffn=True)
+    with pytest.raises(B.MoeError):
+        B.moe_grouped_ffn_gather(buf.shape, args[0], None, buf.offsets, args[2], args[3], args[4],
+                                 buf.h, buf.y_perm)
+    # entries outside [0, T*k) are clamped to a valid row: values unspecified, no fault
+    bad = buf.src_assign.clone()
+    bad[::7] = 1 << 30
+    bad[3::11] = -5
+    B.moe_grouped_ffn_gather(buf.shape, args[0], bad, buf.offsets, args[2], args[3], args[4], buf.h,
+                             buf.y_perm)
+    torch.cuda.synchronize()
+    assert np.isfinite(orc.to_f64(host(buf.y_perm))).all()
