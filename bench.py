@@ -175,7 +175,7 @@ def main():
     consumers = None
     if not args.no_consumers:
         pred = layer.LoadPredictor(cfg.T, cfg.d, cfg.E, cfg.k, cfg.dtype, cfg.renorm,
-                                   max_extra_replicas=cfg.E)
+                                   max_extra_replicas=cfg.E, n_gpus=8)
         w_pred = layer.to_device(si.make_layer(
             si.small_config("predictor_gate", T=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, F=cfg.F,
                             dtype=cfg.dtype, renorm=cfg.renorm, seed=cfg.seed + 1),
@@ -227,7 +227,7 @@ def main():
                         "cv_after": cv_after, "extra_replicas": extra},
             "predictor_pass_us": pred_us,
             "predictor_pass": "moe_route with a second seeded gate matrix + counts + Algorithm 1 + "
-                              "replica segments, alone on the stream",
+                              "replica segments + Algorithm 2 for 8 GPUs, alone on the stream",
             "ms_per_step_with_predictor_on_side_stream": ms_with,
             "added_ms_per_step": ms_with - ms_per_step,
             "paper_prediction_delay_ms": "< 0.2 per layer (Section 6.6, other hardware)",

@@ -184,6 +184,35 @@ int moe_replica_segments(int32_t E, const int32_t* offsets, const int32_t* repli
                          int32_t max_segments, int32_t* seg_offsets, int32_t* seg_expert,
                          int32_t* n_segments, void* hip_stream);
 
+/*
+ * Expert Placement (Algorithm 2, Section 4.3): the GPU of every expert replica of a layer.
+ * Replicas are taken from the most to the least loaded (a replica of expert e carries
+ * loads[e] / replicas[e]; equal loads in ascending (expert, replica) order).  A replica that
+ * the previous round placed and that is still alive keeps its GPU (warm start); any other
+ * joins the GPU with the smallest aggregated load so far (equal loads: the lowest index);
+ * the GPU's load then grows by the replica's load (fp64, in placement order).
+ *   loads, replicas [E]      as for moe_scale_replicas / its output
+ *   n_gpus                   1 .. 64
+ *   prev_replicas [E], prev_gpu [sum of prev_replicas]
+ *                            optional (both NULL = no previous round): the previous round's
+ *                            replica counts and its gpu_of output (expert-major: replica r of
+ *                            expert e at index prev_replicas[0] + .. + prev_replicas[e-1] + r);
+ *                            -1 = that replica is no longer alive.  Replica indices at or above
+ *                            the previous count are new (cold)
+ *   gpu_slots [n_gpus]       optional (NULL = unlimited): replicas each GPU can hold; a GPU
+ *                            without a free slot takes no replica, warm or not; a replica that
+ *                            finds no free slot anywhere gets -1
+ *   gpu_of [max_segments]    GPU per replica, in the segment order of moe_replica_segments; only
+ *                            the first min(S, max_segments) entries are written
+ *   gpu_load [n_gpus] double, gpu_count [n_gpus] int32, n_warm [1] int32
+ * E <= 256; at most E + MOE_MAX_EXTRA_REPLICAS replicas are placed (later ones are skipped and
+ * their entries not written).  One small launch; no host synchronisation.
+ */
+int moe_place_replicas(int32_t E, const int32_t* loads, const int32_t* replicas, int32_t n_gpus,
+                       const int32_t* prev_replicas, const int32_t* prev_gpu,
+                       const int32_t* gpu_slots, int32_t max_segments, int32_t* gpu_of,
+                       double* gpu_load, int32_t* gpu_count, int32_t* n_warm, void* hip_stream);
+
 /* Static, human-readable text for a status code. */
 const char* moe_strerror(int code);
 

@@ -20,6 +20,7 @@ _lib = None
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",
            "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
            "moe_grouped_ffn_gather_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
+           "moe_place_replicas",
            "moe_strerror")
 MOE_MAX_EXTRA_REPLICAS = 65536
 
@@ -64,6 +65,8 @@ def load():
                                        ctypes.c_double, i32p, vp, vp]
     lib.moe_replica_segments.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p,
                                          i32p, vp]
+    lib.moe_place_replicas.argtypes = [ctypes.c_int32, i32p, i32p, ctypes.c_int32, i32p, i32p, i32p,
+                                       ctypes.c_int32, i32p, vp, i32p, i32p, vp]
     lib.moe_strerror.argtypes = [ctypes.c_int]
     lib.moe_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
@@ -169,3 +172,12 @@ def moe_replica_segments(E, offsets, replicas, max_segments, seg_offsets, seg_ex
            load().moe_replica_segments(int(E), _ptr(offsets), _ptr(replicas), int(max_segments),
                                        _ptr(seg_offsets), _ptr(seg_expert), _ptr(n_segments),
                                        _stream(stream)))
+
+
+def moe_place_replicas(E, loads, replicas, n_gpus, prev_replicas, prev_gpu, gpu_slots, max_segments,
+                       gpu_of, gpu_load, gpu_count, n_warm, stream=None):
+    _check("moe_place_replicas",
+           load().moe_place_replicas(int(E), _ptr(loads), _ptr(replicas), int(n_gpus),
+                                     _ptr(prev_replicas), _ptr(prev_gpu), _ptr(gpu_slots),
+                                     int(max_segments), _ptr(gpu_of), _ptr(gpu_load),
+                                     _ptr(gpu_count), _ptr(n_warm), _stream(stream)))

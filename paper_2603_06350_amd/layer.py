@@ -82,7 +82,7 @@ class LoadPredictor:
     moe_scale_replicas -> moe_replica_segments.  Outputs stay in `counts`, `offsets`, `replicas`,
     `cv` ([before, after]), `seg_offsets`, `seg_expert`, `n_segments`."""
 
-    def __init__(self, T, d, E, k, dtype, renorm, max_extra_replicas, device="cuda"):
+    def __init__(self, T, d, E, k, dtype, renorm, max_extra_replicas, n_gpus=0, device="cuda"):
         # F does not enter any of the calls used here; 8 keeps the shape valid for both dtypes
         self.shape = B.make_shape(T, d, E, k, 8, dtype, renorm)
         self.E = E
@@ -103,6 +103,15 @@ class LoadPredictor:
         self.seg_offsets = torch.empty((self.max_segments + 1,), dtype=torch.int32, **kw)
         self.seg_expert = torch.empty((self.max_segments,), dtype=torch.int32, **kw)
         self.n_segments = torch.empty((1,), dtype=torch.int32, **kw)
+        # Algorithm 2 (optional): two sets of placement buffers, the previous round's is the warm set
+        self.n_gpus = int(n_gpus)
+        self.round = 0
+        if self.n_gpus > 0:
+            self.gpu_of = [torch.full((self.max_segments,), -1, dtype=torch.int32, **kw) for _ in range(2)]
+            self.placed_replicas = [torch.zeros((E,), dtype=torch.int32, **kw) for _ in range(2)]
+            self.gpu_load = torch.empty((self.n_gpus,), dtype=torch.float64, **kw)
+            self.gpu_count = torch.empty((self.n_gpus,), dtype=torch.int32, **kw)
+            self.n_warm = torch.empty((1,), dtype=torch.int32, **kw)
 
     def enqueue(self, x, w_pred, gate_bias=None, cv_threshold=0.2, stream=None):
         s = torch.cuda.current_stream() if stream is None else stream
@@ -114,3 +123,13 @@ class LoadPredictor:
                              self.cv, s)
         B.moe_replica_segments(self.E, self.offsets, self.replicas, self.max_segments,
                                self.seg_offsets, self.seg_expert, self.n_segments, s)
+        if self.n_gpus > 0:
+            cur, prev = self.round & 1, (self.round & 1) ^ 1
+            with torch.cuda.stream(s):          # keep this round's counts for the next round's warm set
+                self.placed_replicas[cur].copy_(self.replicas, non_blocking=True)
+            B.moe_place_replicas(self.E, self.counts, self.replicas, self.n_gpus,
+                                 self.placed_replicas[prev] if self.round > 0 else None,
+                                 self.gpu_of[prev] if self.round > 0 else None, None,
+                                 self.max_segments, self.gpu_of[cur], self.gpu_load, self.gpu_count,
+                                 self.n_warm, s)
+            self.round += 1

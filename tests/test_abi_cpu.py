@@ -121,6 +121,13 @@ def test_scaler_calls_validate_on_the_host(lib):
         (lambda: B.moe_replica_segments(8, one, one, -1, one, one, one), -1),
         (lambda: B.moe_replica_segments(8, one, one, 16, one, one, None), -1),
         (lambda: B.moe_replica_segments(300, one, one, 16, one, one, one), -2),
+        (lambda: B.moe_place_replicas(0, one, one, 2, None, None, None, 8, one, one, one, one), -1),
+        (lambda: B.moe_place_replicas(8, one, one, 0, None, None, None, 8, one, one, one, one), -1),
+        (lambda: B.moe_place_replicas(8, None, one, 2, None, None, None, 8, one, one, one, one), -1),
+        (lambda: B.moe_place_replicas(8, one, one, 2, one, None, None, 8, one, one, one, one), -1),
+        (lambda: B.moe_place_replicas(8, one, one, 2, None, None, None, -1, one, one, one, one), -1),
+        (lambda: B.moe_place_replicas(8, one, one, 65, None, None, None, 8, one, one, one, one), -2),
+        (lambda: B.moe_place_replicas(300, one, one, 2, None, None, None, 8, one, one, one, one), -2),
     ]
     for call, code in cases:
         with pytest.raises(B.MoeError) as ei:

@@ -201,3 +201,131 @@ def test_predictor_on_a_side_stream_next_to_the_layer():
     assert np.array_equal(pred.seg_expert.cpu().numpy()[:S], who_ref)
     # the prediction of a gate that differs from the layer's own is a different load vector
     assert not np.array_equal(counts_p, alone["counts"])
+
+
+# ----------------------------------------------------------------------------- placement
+from oracle import placer_oracle as pl  # noqa: E402
+
+
+def gpu_place(loads, replicas, G, prev_offsets=None, prev_gpu=None, slots=None, max_segments=None):
+    E = len(loads)
+    S = int(np.sum(replicas))
+    max_segments = S if max_segments is None else max_segments
+    i32 = lambda a: None if a is None else torch.tensor(np.asarray(a, dtype=np.int32), device="cuda")
+    gpu_of = torch.full((max(max_segments, 1),), -9, dtype=torch.int32, device="cuda")
+    load = torch.full((G,), -1.0, dtype=torch.float64, device="cuda")
+    count = torch.full((G,), -1, dtype=torch.int32, device="cuda")
+    warm = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    d_prev_gpu = i32(prev_gpu)
+    if prev_gpu is not None and len(prev_gpu) == 0:        # a zero-size tensor has no address
+        d_prev_gpu = torch.zeros(1, dtype=torch.int32, device="cuda")
+    prev_replicas = None if prev_offsets is None else np.diff(np.asarray(prev_offsets))
+    B.moe_place_replicas(E, i32(loads), i32(replicas), G, i32(prev_replicas), d_prev_gpu, i32(slots),
+                         max_segments, gpu_of, load, count, warm)
+    torch.cuda.synchronize()
+    return gpu_of.cpu().numpy(), load.cpu().numpy(), count.cpu().numpy(), int(warm.item())
+
+
+def check_place(loads, replicas, G, prev_offsets=None, prev_gpu=None, slots=None):
+    want_of, want_load, want_count, want_warm = pl.expert_placement(loads, replicas, G, prev_offsets,
+                                                                    prev_gpu, slots)
+    got_of, got_load, got_count, got_warm = gpu_place(loads, replicas, G, prev_offsets, prev_gpu, slots)
+    assert np.array_equal(got_of[:len(want_of)], want_of)
+    assert np.array_equal(got_count, want_count) and got_warm == want_warm
+    assert np.array_equal(got_load, want_load)            # the same fp64 sums in the same order
+    return got_of
+
+
+def test_place_replicas_hand_worked():
+    assert check_place([6, 4, 2], [2, 1, 1], 2).tolist() == [1, 1, 0, 0]
+    assert check_place([6, 4, 2], [2, 1, 1], 2, [0, 1, 2, 3], [-1, 1, -1]).tolist() == [0, 0, 1, 1]
+    assert check_place([10, 9], [1, 1], 2, [0, 1, 2], [0, 0]).tolist() == [0, 0]
+    assert check_place([6, 4, 2], [2, 1, 1], 2, slots=[1, 3]).tolist() == [1, 1, 0, 1]
+    assert check_place([6, 4, 2], [2, 1, 1], 2, slots=[1, 1]).tolist() == [1, -1, 0, -1]
+    assert check_place([5, 4], [1, 1], 2, [0, 1, 2], [0, 0], slots=[1, 1]).tolist() == [0, 1]
+    check_place([0, 0, 0], [1, 2, 1], 3)                                   # zero loads are placed too
+    check_place([7], [5], 1)                                               # one GPU
+
+
+def test_place_replicas_matches_oracle():
+    rng = np.random.default_rng(53)
+    for trial in range(40):
+        E = int(rng.choice([1, 3, 8, 16, 64, 200, 256]))
+        loads = si.zipf_loads(E, int(rng.integers(E, 200000)), float(rng.uniform(0.2, 1.8)), 500 + trial)
+        replicas, _ = sc.expert_scaling(loads, 1, int(rng.integers(0, 2 * E + 1)), 0.1)
+        G = int(rng.choice([1, 2, 7, 8, 16, 64]))
+        kind = trial % 4
+        prev_offsets = prev_gpu = slots = None
+        if kind in (1, 3):
+            prev_r = rng.integers(0, 4, size=E)
+            prev_offsets = np.concatenate([[0], np.cumsum(prev_r)])
+            prev_gpu = rng.integers(-1, G, size=int(prev_offsets[-1]))
+        if kind in (2, 3):
+            S = int(replicas.sum())
+            slots = rng.integers(0, max(2, 2 * S // G + 2), size=G)
+        check_place(loads, replicas, G, prev_offsets, prev_gpu, slots)
+
+
+def test_place_replicas_respects_the_output_bound():
+    loads, replicas = [9, 7, 5, 3], [3, 2, 1, 1]
+    want, _, _, _ = pl.expert_placement(loads, replicas, 2)
+    got, _, count, _ = gpu_place(loads, replicas, 2, max_segments=4)
+    assert np.array_equal(got[:4], want[:4]) and count.sum() == 7          # all placed, four reported
+
+
+def test_scale_segments_place_chain_on_device():
+    """counts -> Algorithm 1 -> segments -> Algorithm 2, one stream, no host round trip; then a second
+    round that re-uses the first round's placement as its warm set."""
+    E, G = 64, 8
+    loads = si.zipf_loads(E, 49152, 1.2, 77)
+    d_loads = torch.tensor(loads.astype(np.int32), device="cuda")
+    rep = torch.zeros(E, dtype=torch.int32, device="cuda")
+    S_max = E + 32
+    gpu_of = torch.full((S_max,), -9, dtype=torch.int32, device="cuda")
+    load = torch.zeros(G, dtype=torch.float64, device="cuda")
+    count = torch.zeros(G, dtype=torch.int32, device="cuda")
+    warm = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.moe_scale_replicas(E, d_loads, 1, 32, 0.2, rep, None)
+    B.moe_place_replicas(E, d_loads, rep, G, None, None, None, S_max, gpu_of, load, count, warm)
+    torch.cuda.synchronize()
+    want_rep, _ = sc.expert_scaling(loads, 1, 32, 0.2)
+    want_of, want_load, want_count, _ = pl.expert_placement(loads, want_rep, G)
+    S = int(want_rep.sum())
+    assert np.array_equal(rep.cpu().numpy(), want_rep)
+    assert np.array_equal(gpu_of.cpu().numpy()[:S], want_of)
+    assert np.array_equal(load.cpu().numpy(), want_load)
+    # balanced: no GPU is above the mean by more than the largest replica load
+    per = (loads / want_rep).max()
+    assert want_load.max() - want_load.mean() <= per
+    # second round: a different batch, the previous placement kept alive
+    loads2 = si.zipf_loads(E, 49152, 1.2, 78)
+    prev_offsets = np.concatenate([[0], np.cumsum(want_rep)]).astype(np.int32)
+    want_rep2, _ = sc.expert_scaling(loads2, 1, 32, 0.2)
+    want2 = pl.expert_placement(loads2, want_rep2, G, prev_offsets, want_of)
+    got2 = gpu_place(loads2, want_rep2, G, prev_offsets, want_of)
+    assert np.array_equal(got2[0][:len(want2[0])], want2[0]) and got2[3] == want2[3] and want2[3] > 0
+
+
+def test_predictor_with_placement_keeps_warm_replicas_over_rounds():
+    cfg = si.small_config("pred_place", T=900, d=256, E=16, k=2, F=128, zipf_alpha=1.2, zipf_scale=0.9)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    x, wg, bias = (layer.to_device(L[n]) for n in ("x", "w_gate", "gate_bias"))
+    G = 4
+    pred = layer.LoadPredictor(cfg.T, cfg.d, cfg.E, cfg.k, cfg.dtype, cfg.renorm, max_extra_replicas=8,
+                               n_gpus=G)
+    idx, _, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm, L["gate_bias"])
+    counts = np.bincount(idx.ravel(), minlength=cfg.E)
+    rep, _ = sc.expert_scaling(counts, 1, 8, 0.2)
+    first = pl.expert_placement(counts, rep, G)
+    pred.enqueue(x, wg, bias, 0.2)
+    torch.cuda.synchronize()
+    S = int(rep.sum())
+    assert np.array_equal(pred.replicas.cpu().numpy(), rep)
+    assert np.array_equal(pred.gpu_of[0].cpu().numpy()[:S], first[0]) and int(pred.n_warm.item()) == 0
+    # same batch again: every replica is warm and nothing moves
+    pred.enqueue(x, wg, bias, 0.2)
+    torch.cuda.synchronize()
+    second = pl.expert_placement(counts, rep, G, np.concatenate([[0], np.cumsum(rep)]), first[0])
+    assert second[3] == S and np.array_equal(second[0], first[0])
+    assert np.array_equal(pred.gpu_of[1].cpu().numpy()[:S], second[0]) and int(pred.n_warm.item()) == S
+    assert np.array_equal(pred.gpu_load.cpu().numpy(), second[1])
