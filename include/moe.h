@@ -103,6 +103,12 @@ int moe_count_and_permute(const moe_shape_t* shape, const void* x, const int32_t
  * x_perm [T*k,d]; w1, w3 [E,F,d]; w2 [E,d,F]; h [T*k,F] (caller-provided scratch,
  * holds the activations on return); y_perm [T*k,d]; all in `dtype`; offsets [E+1]
  * int32 on the device (read by the kernels; no host round trip).
+ * Streams: for layers with large experts (T*k/E >= 128) part of the work is enqueued on
+ * one library-owned side stream per device (default priority, created at first use, kept
+ * for the life of the process), forked from `hip_stream` with an event and joined back with
+ * another before the call returns.  For the caller all work is ordered on `hip_stream` as
+ * usual, and a stream capture of `hip_stream` records the fork and join as graph edges.
+ * Calls from several host threads are safe; their enqueue sequences are serialised.
  */
 int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
                     const void* w1, const void* w3, const void* w2, void* h, void* y_perm,

@@ -1,6 +1,9 @@
 // moe_grouped_ffn: the expert computation that dominates the MoE layer (Section 3.2).
 // For every expert e and row r of its segment [offsets[e], offsets[e+1]):
 //   h[r] = silu(W1_e x_perm[r]) * (W3_e x_perm[r]),   y_perm[r] = W2_e h[r].
+// The activation rows come either from a permuted copy x_perm, or straight from x through the
+// dispatch's src_assign map (moe_grouped_ffn_gather: row r is x[src_assign[r] / k]); the map only
+// changes the per-lane row offset of the activation loads.
 //
 // Two GEMMs: a gated one (W1 and W3 tiles side by side, SwiGLU applied to the fp32
 // accumulators, h stored once) and a plain one for W2.  Both are ragged grouped
@@ -11,16 +14,19 @@
 //   small  block tile 64 x 256: remainders of at most 64 rows (the tail of a large
 //          expert, or all of a small one: decode-shaped layers live here).
 // A small tile has little arithmetic per weight byte, so it is paced by memory
-// latency: it runs a four-stage LDS ring with three stages of loads in flight.
+// latency: it runs a four-stage LDS ring with three stages of loads in flight.  For
+// layers with large experts the small launches run on a side stream next to the main
+// ones (they stream weights from HBM while the main tiles are MFMA/L2 bound).
 //
 // bf16 kernels (gfx950): 512 threads = 8 waves, two per SIMD.  K step 64: both
 // operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
-// global -> LDS with the direct 16-byte-per-lane loads (no register staging); a wave
-// instruction fills 8 rows, and the chunk a lane fetches is XOR-swizzled by row so
-// that the 16-byte LDS reads of a 16-row MFMA operand are bank-conflict free.  The
-// weight fragment is the MFMA "A" operand and the activation fragment "B": a lane then
-// owns 4 consecutive output columns of one output row.  v_mfma_f32_16x16x32_bf16, fp32
-// accumulators (on this chip it sustains a higher rate than the 32x32x16 form).
+// global -> LDS with 16-byte-per-lane buffer loads that write LDS directly (no register
+// staging); a wave instruction fills 8 rows, and the chunk a lane fetches is
+// XOR-swizzled by row so that the 16-byte LDS reads of a 16-row MFMA operand are
+// bank-conflict free.  The weight fragment is the MFMA "A" operand and the activation
+// fragment "B": a lane then owns 4 consecutive output columns of one output row.
+// v_mfma_f32_16x16x32_bf16, fp32 accumulators (on this chip it sustains a higher rate
+// than the 32x32x16 form).
 //
 // Work-group ids are remapped so that each XCD (ids are dealt round-robin to the 8
 // XCDs) walks a contiguous range of the tile list with the m-tiles of one weight
