@@ -88,14 +88,18 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int lane = lane_id();
   const int per = (E + MOE_WAVE - 1) / MOE_WAVE;  // <= 4
   const int e0 = lane * per;
-  int mt[4];
+  int mt[4], ob[4], oe[4];                       // tiles, first and end row of this lane's experts
   int local = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int e = e0 + i;
     int t = 0;
+    ob[i] = 0;
+    oe[i] = 0;
     if (i < per && e < E) {
-      const int c = max(offsets[e + 1] - offsets[e], 0);
+      ob[i] = offsets[e];
+      oe[i] = offsets[e + 1];
+      const int c = max(oe[i] - ob[i], 0);
       const int full = c / bm, rem = c % bm;
       if (mode == TILES_ALL) t = full + (rem > 0 ? 1 : 0);
       else if (mode == TILES_MAIN) t = full + (rem > SMALL_ROWS ? 1 : 0);
@@ -118,7 +122,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int vid = xcd * per_xcd + slot;
   if (slot >= per_xcd || vid >= total) return false;
   int run = incl - local;
-  int found_e = -1, found_local = 0, found_mt = 1;
+  int found_e = -1, found_local = 0, found_mt = 1, found_ob = 0, found_oe = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int s = run * n_tiles;
@@ -126,6 +130,8 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
       found_e = e0 + i;
       found_local = vid - s;
       found_mt = mt[i];
+      found_ob = ob[i];
+      found_oe = oe[i];
     }
     run += mt[i];
   }
@@ -136,8 +142,9 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int loc = __builtin_amdgcn_readfirstlane(__shfl(found_local, src));
   const int m_tiles = __builtin_amdgcn_readfirstlane(__shfl(found_mt, src));
   const int m_idx = loc % m_tiles;
-  const int seg_begin = max(offsets[e], 0);
-  const int seg_end = min(offsets[e + 1], p.rows);
+  // the lane that owns the expert already holds its row range: no second trip to memory
+  const int seg_begin = max(__builtin_amdgcn_readfirstlane(__shfl(found_ob, src)), 0);
+  const int seg_end = min(__builtin_amdgcn_readfirstlane(__shfl(found_oe, src)), p.rows);
   tc.e = e;
   tc.n_tile = loc / m_tiles;
   if (mode == TILES_SMALL) {
