@@ -1,5 +1,6 @@
-"""GPU parity at the full sizes of the five named workloads, in the launch configuration
-bench.py times (the four calls chained on one stream, buffers from MoeBuffers).
+"""GPU parity at the full sizes of the five named workloads, in the launch configurations
+bench.py times (the calls chained on one stream, buffers from MoeBuffers; both the four-call form
+with a written x_perm and the default form in which the FFN reads x through the permutation map).
 
 Routing, expert load and the permutation are compared with the full oracle on every
 token (the oracle's routing is cheap at any size).  The expert FFN and the combine are
@@ -30,9 +31,21 @@ def _gpu():
 def run_layer(cfg, L):
     dev = {n: layer.to_device(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")}
     buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
-    buf.forward(dev["x"], dev["w_gate"], dev["w1"], dev["w3"], dev["w2"],
-                gate_bias=layer.to_device(L["gate_bias"]), export_scores=True)
+    bias = layer.to_device(L["gate_bias"])
+    # the four-call form first (it writes x_perm, which check_routing_and_dispatch compares) ...
+    buf.forward(dev["x"], dev["w_gate"], dev["w1"], dev["w3"], dev["w2"], gate_bias=bias,
+                export_scores=True)
     torch.cuda.synchronize()
+    first = {n: getattr(buf, n).clone() for n in ("h", "y_perm", "y")}
+    for n in first:
+        getattr(buf, n).zero_()
+    # ... then the form bench.py times by default: the up-projection reads x through the permutation
+    # map.  Its outputs, which the sampled checks below look at, must be the same bits.
+    buf.forward(dev["x"], dev["w_gate"], dev["w1"], dev["w3"], dev["w2"], gate_bias=bias,
+                export_scores=True, gather_in_ffn=True)
+    torch.cuda.synchronize()
+    for n, v in first.items():
+        assert torch.equal(getattr(buf, n), v), f"{n} differs between the two forms of the FFN call"
     return buf
 
 
