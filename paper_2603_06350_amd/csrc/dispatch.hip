@@ -3,7 +3,8 @@
 // of the T*k assignments and the row gather that realises the single-GPU "scatter"
 // of Section 2.2.
 //
-// Three launches on the caller's stream, no host synchronisation:
+// Three launches on the caller's stream (two for batches of at most 1024 assignments, where
+// rank_small_kernel replaces 1 and 2), no host synchronisation:
 //   1. hist_kernel   one thread per token; LDS histogram of the block's
 //                    assignments -> partial[block][expert]              (integer)
 //   2. rank_kernel   same token partition.  Every block sums `partial` to get
@@ -66,16 +67,34 @@ __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ t
     const int n16 = E * NTH * 2 / 16;
     for (int i = tid; i < n16; i += NTH) z[i] = make_uint4(0, 0, 0, 0);
   }
-  // totals per expert and the part that belongs to earlier blocks
+  // totals per expert and the part that belongs to earlier blocks: every thread takes a strided
+  // share of partial[NB][E] (coalesced, several loads in flight) and adds it into LDS; integer
+  // sums, so the order of the atomics does not matter
   for (int e = tid; e < E; e += NTH) {
-    int total = 0, before = 0;
-    for (int bb = 0; bb < NB; ++bb) {
-      const int v = partial[static_cast<int64_t>(bb) * E + e];
-      total += v;
-      before += (bb < b) ? v : 0;
+    tot[e] = 0;
+    base[e] = 0;
+  }
+  __syncthreads();
+  {
+    const int n = NB * E;
+    constexpr int UNR = 8;
+    for (int i0 = tid; i0 < n; i0 += UNR * NTH) {
+      int v[UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int i = i0 + u * NTH;
+        v[u] = i < n ? partial[i] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int i = i0 + u * NTH;
+        if (i < n && v[u] != 0) {
+          const int e = i % E, bb = i / E;
+          atomicAdd(&tot[e], v[u]);
+          if (bb < b) atomicAdd(&base[e], v[u]);
+        }
+      }
     }
-    tot[e] = total;
-    base[e] = before;
   }
   __syncthreads();
   // exclusive scan of tot over experts by wave 0 (E <= 256: at most 4 per lane)
@@ -156,6 +175,74 @@ __global__ __launch_bounds__(NTH) void rank_kernel(const int32_t* __restrict__ t
   }
 }
 
+// Small batches (T*k <= RS_MAX_A): one block does the whole dispatch.  The rank of an assignment
+// is counted directly, as the number of earlier assignments of the same expert (all assignments
+// sit in LDS and are read as broadcasts), so there is no table to clear or scan and one launch
+// replaces two.
+constexpr int RS_MAX_A = 1024;
+__global__ __launch_bounds__(256) void rank_small_kernel(const int32_t* __restrict__ topk_idx, int A,
+                                                         int E, int32_t* __restrict__ counts,
+                                                         int32_t* __restrict__ offsets,
+                                                         int32_t* __restrict__ dst_row,
+                                                         int32_t* __restrict__ src_assign) {
+  __shared__ __align__(16) int32_t idx[RS_MAX_A];
+  __shared__ int32_t cnt[MOE_MAX_E];
+  __shared__ int32_t off[MOE_MAX_E + 1];
+  const int tid = threadIdx.x;
+  const int lane = tid & (MOE_WAVE - 1);
+  for (int e = tid; e < E; e += 256) cnt[e] = 0;
+  for (int a = tid; a < RS_MAX_A; a += 256) {
+    int e = a < A ? topk_idx[a] : -1;
+    if (static_cast<unsigned>(e) >= static_cast<unsigned>(E)) e = -1;   // invalid: never matches
+    idx[a] = e;
+  }
+  __syncthreads();
+  for (int a = tid; a < A; a += 256)
+    if (idx[a] >= 0) atomicAdd(&cnt[idx[a]], 1);
+  __syncthreads();
+  if (tid < MOE_WAVE) {                         // exclusive scan over experts by wave 0
+    const int per = (E + MOE_WAVE - 1) / MOE_WAVE;
+    const int e0 = lane * per;
+    int local = 0;
+    for (int i = 0; i < per; ++i)
+      if (e0 + i < E) local += cnt[e0 + i];
+    int incl = local;
+    for (int o = 1; o < MOE_WAVE; o <<= 1) {
+      const int up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    int run = incl - local;
+    for (int i = 0; i < per; ++i) {
+      const int e = e0 + i;
+      if (e < E) {
+        off[e] = run;
+        counts[e] = cnt[e];
+        offsets[e] = run;
+        run += cnt[e];
+      }
+    }
+    if (lane == MOE_WAVE - 1) offsets[E] = incl;
+  }
+  __syncthreads();
+  const int a4 = (A + 3) & ~3;
+  for (int a = tid; a < A; a += 256) {
+    const int e = idx[a];
+    if (e < 0) {
+      dst_row[a] = 0;                           // invalid expert index: value unspecified, in bounds
+      continue;
+    }
+    int r = 0;
+    for (int b0 = 0; b0 < a4; b0 += 4) {
+      const int4 v = *reinterpret_cast<const int4*>(idx + b0);
+      r += (v.x == e && b0 < a) + (v.y == e && b0 + 1 < a) + (v.z == e && b0 + 2 < a) +
+           (v.w == e && b0 + 3 < a);
+    }
+    const int dst = off[e] + r;
+    dst_row[a] = dst;
+    src_assign[dst] = a;
+  }
+}
+
 // One wave per token.  row16 = row size in 16-byte units.
 __global__ __launch_bounds__(256) void gather_kernel(const uint4* __restrict__ x,
                                                      const int32_t* __restrict__ dst_row,
@@ -225,7 +312,10 @@ extern "C" int moe_count_and_permute(const moe_shape_t* shape, const void* x,
   const size_t lds = static_cast<size_t>(E) * nth * 2 + static_cast<size_t>(E) * 8;
   // T == 0 still defines counts = 0 and offsets = 0: one block with no tokens does that.
   const int grid = nb > 0 ? nb : 1;
-  if (nth == 256) {
+  if (static_cast<int64_t>(T) * k <= moe::RS_MAX_A) {
+    hipLaunchKernelGGL(moe::rank_small_kernel, dim3(1), dim3(256), 0, st, topk_idx, T * k, E, counts,
+                       offsets, dst_row, src_assign);
+  } else if (nth == 256) {
     static bool attr_set = false;
     if (!attr_set) {
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(moe::rank_kernel<256>),
