@@ -8,10 +8,10 @@
 // each runs v_mfma_f32_16x16x32_bf16 on its slice straight from global memory (x is
 // read exactly once from HBM, 16 B per lane; w_gate is small and stays in L2), the
 // eight partial score tiles meet in LDS and are summed in a fixed order, so the
-// scores are deterministic.  Each wave then routes its tokens by rank counting:
-// every lane compares its scores with all E scores (broadcast LDS reads), and the
-// expert preceded by r others (larger score, or equal score and lower index) is the
-// r-th pick; the softmax weights come from the same scores.
+// scores are deterministic.  Each wave then routes its tokens: k+1 rounds of "largest
+// remaining score, lowest index among equals" (a DPP maximum over the wave, then a
+// ballot on equality), which also yields the gap from every chosen score to its
+// nearest neighbour; the softmax weights come from the same scores.
 //
 // The integer choice must not depend on the order of an fp32 sum.  After the fast
 // pass a token is "ambiguous" if one of its k chosen scores has another score within
@@ -21,6 +21,8 @@
 // products and fp64 sums rounded once to fp32, which is the correctly rounded score
 // up to fp64 rounding, and the token is routed again.  fp32 inputs always take the
 // exact path for all experts.
+#include <type_traits>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -46,97 +48,102 @@ __device__ __forceinline__ float wave_max(float v) {
 
 constexpr int RT_CMAX = 16;   // candidate experts re-scored exactly for an ambiguous token
 
-// Value of s[q] in the lane/slot where hit[q] is true (exactly one such slot is expected);
-// `dflt` if there is none.  Wave-uniform result.
-template <int QE>
-__device__ __forceinline__ float pick_where(const float (&s)[QE], const bool (&hit)[QE], float dflt) {
-  float r = dflt;
-#pragma unroll
-  for (int q = 0; q < QE; ++q) {
-    const unsigned long long m = __ballot(hit[q]);
-    if (m != 0ull) r = __shfl(s[q], __ffsll(static_cast<long long>(m)) - 1);
-  }
-  return r;
+// Largest value of a wave, on every lane: four DPP steps make each row of 16 lanes hold its
+// maximum (lane swaps inside quads, then the half-row and row mirrors), two row broadcasts carry
+// it across the four rows into lane 63.
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  auto step = [](float x, auto ctrl, auto rows) {
+    const int moved = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x),
+                                                  decltype(ctrl)::value, decltype(rows)::value, 0xF, false);
+    return fmaxf(x, __int_as_float(moved));
+  };
+  using std::integral_constant;
+  v = step(v, integral_constant<int, 0xB1>{}, integral_constant<int, 0xF>{});    // quad_perm [1,0,3,2]
+  v = step(v, integral_constant<int, 0x4E>{}, integral_constant<int, 0xF>{});    // quad_perm [2,3,0,1]
+  v = step(v, integral_constant<int, 0x141>{}, integral_constant<int, 0xF>{});   // row_half_mirror
+  v = step(v, integral_constant<int, 0x140>{}, integral_constant<int, 0xF>{});   // row_mirror
+  v = step(v, integral_constant<int, 0x142>{}, integral_constant<int, 0xA>{});   // row_bcast15 -> rows 1, 3
+  v = step(v, integral_constant<int, 0x143>{}, integral_constant<int, 0xC>{});   // row_bcast31 -> rows 2, 3
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
-// Routes one token with a full wave.  s[q] is the score of expert lane + 64 q; srow is a
-// per-wave LDS row of at least (E rounded up to 4) floats.
-// Selection by rank counting: every lane compares its scores with all E scores (broadcast LDS
-// reads, no cross-lane dependency chain); the expert whose score is preceded by r others
-// (larger score, or equal score and lower index) is the r-th pick.
+// Routes one token with a full wave.  s[q] is the score of expert lane + 64 q.
+// Selection: k (+1) rounds of "largest remaining score, lowest index among equals": the value by
+// a DPP maximum over the wave, the index by a ballot on equality, both wave-uniform, so every
+// pick costs a few dozen instructions whatever E is.  The extra round fetches the best score
+// that is NOT chosen: the picks come out in descending order, so a chosen score's nearest
+// neighbour is the pick before or after it.
 // With `check`: if any of the k chosen experts has another score within the fast pass's error
 // margin, nothing is written; the experts that could still be among the first k are listed in
 // cand[] and their number is returned (RT_CMAX + 1 if there are too many).  Otherwise returns 0.
 template <int QE>
 __device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, int k, int renorm,
-                           int64_t t, float* __restrict__ srow, int* __restrict__ cand,
-                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                           float* __restrict__ scores_out) {
+                           int64_t t, int* __restrict__ cand, int32_t* __restrict__ topk_idx,
+                           float* __restrict__ topk_w, float* __restrict__ scores_out) {
   const int lane = lane_id();
-  const int e4 = (E + 3) & ~3;
-#pragma unroll
-  for (int q = 0; q < QE; ++q) {
-    const int e = lane + MOE_WAVE * q;
-    if (e < e4) srow[e] = (e < E) ? s[q] : -INFINITY;
-  }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: LDS writes land before the reads
+  bool valid[QE], taken[QE], chosen[QE];
   int rank[QE];
-  float mingap[QE];
-#pragma unroll
-  for (int q = 0; q < QE; ++q) {
-    rank[q] = 0;
-    mingap[q] = INFINITY;
-  }
-#pragma unroll 4
-  for (int e2 = 0; e2 < e4; e2 += 4) {
-    const float4 v4 = *reinterpret_cast<const float4*>(srow + e2);
-    const float v[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-#pragma unroll
-      for (int q = 0; q < QE; ++q) {
-        const int e = lane + MOE_WAVE * q;
-        rank[q] += (v[u] > s[q] || (v[u] == s[q] && e2 + u < e)) ? 1 : 0;
-        if (e2 + u != e) mingap[q] = fminf(mingap[q], fabsf(v[u] - s[q]));
-      }
-    }
-  }
-  bool valid[QE], chosen[QE];
 #pragma unroll
   for (int q = 0; q < QE; ++q) {
     valid[q] = lane + MOE_WAVE * q < E;
-    chosen[q] = valid[q] && rank[q] < k;
+    taken[q] = !valid[q];
+    rank[q] = 0x7FFFFFFF;
   }
-  if (check) {
-    bool amb = false;
+  const int picks = E > k ? k + 1 : k;
+  float prev = INFINITY, gap_prev = INFINITY, top = 0.f;
+  bool amb = false;
+  for (int i = 0; i < picks; ++i) {
+    float loc = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < QE; ++q)
+      if (!taken[q]) loc = fmaxf(loc, s[q]);
+    const float v = wave_max_dpp(loc);
+    int e_star = E;                            // lowest index among the remaining scores equal to v
 #pragma unroll
     for (int q = 0; q < QE; ++q) {
-      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(s[q]);
-      amb = amb || (chosen[q] && !(mingap[q] > tol));
+      const unsigned long long m = __ballot(!taken[q] && s[q] == v);
+      if (m != 0ull && e_star == E) e_star = __ffsll(static_cast<long long>(m)) - 1 + MOE_WAVE * q;
     }
-    if (__ballot(amb) != 0ull) {
-      // candidates: every expert whose score is not clearly below the k-th pick's neighbourhood
-      bool is_kth[QE];
 #pragma unroll
-      for (int q = 0; q < QE; ++q) is_kth[q] = valid[q] && rank[q] == (E > k ? k : k - 1);
-      const float thr = pick_where<QE>(s, is_kth, -INFINITY);
-      const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(thr));
-      int n = 0;
-#pragma unroll
-      for (int q = 0; q < QE; ++q) {
-        const bool c = valid[q] && s[q] >= thr - margin;
-        const unsigned long long m = __ballot(c);
-        const int pos = n + __popcll(m & ((1ull << lane) - 1ull));
-        if (c && pos < RT_CMAX) cand[pos] = lane + MOE_WAVE * q;
-        n += __popcll(m);
+    for (int q = 0; q < QE; ++q) {
+      if (lane + MOE_WAVE * q == e_star) {
+        taken[q] = true;
+        if (i < k) rank[q] = i;
       }
-      return n <= RT_CMAX ? n : RT_CMAX + 1;
     }
+    if (i == 0) top = v;
+    if (i >= 1) {
+      // pick i-1 is a chosen one (i-1 <= k-1): its neighbours are picks i-2 and i
+      const float gap = prev - v;
+      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+      amb = amb || !(fminf(gap_prev, gap) > tol);
+      gap_prev = gap;
+    }
+    prev = v;
   }
-  bool is_top[QE];
+  if (picks == k) {                            // E == k: the last chosen score has no lower neighbour
+    const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+    amb = amb || !(gap_prev > tol);
+  }
 #pragma unroll
-  for (int q = 0; q < QE; ++q) is_top[q] = valid[q] && rank[q] == 0;
-  const float m = pick_where<QE>(s, is_top, 0.f);
+  for (int q = 0; q < QE; ++q) chosen[q] = valid[q] && rank[q] < k;
+  if (check && amb) {                          // wave-uniform
+    // candidates: every expert whose score is not clearly below the neighbourhood of the last pick
+    // (the best unchosen score, or the k-th chosen one if every expert is chosen)
+    const float thr = prev;
+    const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(thr));
+    int n = 0;
+#pragma unroll
+    for (int q = 0; q < QE; ++q) {
+      const bool c = valid[q] && s[q] >= thr - margin;
+      const unsigned long long m = __ballot(c);
+      const int pos = n + __popcll(m & ((1ull << lane) - 1ull));
+      if (c && pos < RT_CMAX) cand[pos] = lane + MOE_WAVE * q;
+      n += __popcll(m);
+    }
+    return n <= RT_CMAX ? n : RT_CMAX + 1;
+  }
+  const float m = top;
   float p[QE];
   float psum = 0.f;
 #pragma unroll
@@ -277,7 +284,7 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
 }
 
 // Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][max(E,RT_CMAX)] |
-//              float srow[RT_NW][E4] | int cand[RT_TM][RT_CMAX] | int flag[RT_TM]      (E4 = E rounded up to 4)
+//              int cand[RT_TM][RT_CMAX] | int flag[RT_TM]
 // RPW = tile rows routed per wave: 2 (a full 16-token tile; compile-time so that the two tokens'
 // dependency chains interleave) or 1 (tpb <= 8 tokens per block).
 template <bool BF16, int NT, int RPW>
@@ -288,11 +295,9 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);
-  const int e4 = (E + 3) & ~3;
   const int dn = E > RT_CMAX ? E : RT_CMAX;
   double* dpart = reinterpret_cast<double*>(smem + static_cast<size_t>(RT_NW) * RT_TM * E * 4);
-  float* srow_all = reinterpret_cast<float*>(dpart + RT_NW * dn);
-  int* cand_all = reinterpret_cast<int*>(srow_all + RT_NW * e4);
+  int* cand_all = reinterpret_cast<int*>(dpart + RT_NW * dn);
   int* flag = cand_all + RT_TM * RT_CMAX;
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
@@ -388,8 +393,8 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       if (t < T) {
         float s[QE];
         const float lmax = fast_scores(row, s);
-        amb = route_token<QE>(s, lmax, true, E, k, renorm, t, srow_all + wave * e4,
-                              cand_all + row * RT_CMAX, topk_idx, topk_w, scores_out);
+        amb = route_token<QE>(s, lmax, true, E, k, renorm, t, cand_all + row * RT_CMAX, topk_idx,
+                              topk_w, scores_out);
       }
       if (lane == 0) flag[row] = amb;
     }
@@ -437,17 +442,15 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
           s[q] = static_cast<float>(v);
         }
       }
-      route_token<QE>(s, 0.f, false, E, k, renorm, t, srow_all + wave * e4, nullptr, topk_idx,
-                      topk_w, scores_out);
+      route_token<QE>(s, 0.f, false, E, k, renorm, t, nullptr, topk_idx, topk_w, scores_out);
     }
     __syncthreads();
   }
 }
 
 static size_t route_lds_bytes(int E) {
-  const size_t e4 = (static_cast<size_t>(E) + 3) & ~static_cast<size_t>(3);
   const size_t dn = E > RT_CMAX ? E : RT_CMAX;
-  return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 + RT_NW * e4 * 4 +
+  return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 +
          RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int);
 }
 
