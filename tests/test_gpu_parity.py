@@ -316,6 +316,11 @@ LAYER_CASES = [
     si.small_config("bf16_decode_like", T=32, d=512, E=128, k=8, F=192),
     si.small_config("bf16_skew", T=600, d=256, E=64, k=6, F=128, renorm=0, zipf_alpha=1.2,
                     zipf_scale=0.9, empty_tail=4),
+    si.small_config("bf16_limits", T=100, d=128, E=256, k=64, F=64),       # the largest E and k
+    si.small_config("bf16_top1", T=700, d=128, E=16, k=1, F=192),          # one expert per token
+    si.small_config("bf16_all_experts", T=150, d=128, E=8, k=8, F=64, renorm=0),   # k = E
+    si.small_config("bf16_many_tokens", T=20000, d=64, E=8, k=2, F=64),    # many dispatch blocks
+    si.small_config("f32_odd", T=130, d=100, E=12, k=3, F=52, dtype=si.F32),
 ]
 
 
