@@ -34,7 +34,7 @@ MEASURED_HBM_TRAFFIC = {
                 "source": "profiles/mixtral_layer_all_kernels.md"},
 }
 
-CPU_SAMPLE_TOKENS = {"mixtral": 2048, "finegrained": 2048, "skew": 2048, "decode": 32, "tiny": 64}
+CPU_SAMPLE_TOKENS = {"mixtral": 2048, "phi": 2048, "llama4": 2048, "finegrained": 2048, "skew": 2048, "decode": 32, "tiny": 64}
 
 
 def algorithmic_work(cfg):

@@ -626,7 +626,10 @@ static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
   return launch_status();
 }
 
-static bool big_tiles(const GemmArgs& g, int64_t A) { return A / g.E >= 512; }  // mean rows per expert
+// 256-row main tiles once the mean rows per expert reach 192: an expert with about one tile's
+// worth of rows is then one (partial) tile instead of a 128-row tile plus a remainder that would
+// stream its weights a second time.
+static bool big_tiles(const GemmArgs& g, int64_t A) { return A / g.E >= 192; }
 
 // Main tiles of one grouped GEMM on the MFMA path.
 template <bool GATED>

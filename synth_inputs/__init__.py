@@ -73,6 +73,14 @@ CONFIGS = {
     "decode": LayerConfig("decode", T=32, d=4096, E=128, k=8, F=1536, dtype=BF16, renorm=1,
                           seed=5005, x_std=1.0, w_std=-1.0),
 }
+# The paper's other two evaluation models (its Table 1 gives experts per layer, active experts and
+# parameter totals: Phi-3.5-MoE 2 of 16, 42 B; Llama-4-Scout 1 of 16, 109 B).  Hidden and FFN widths
+# are not in the paper; they are the public model configurations, and with them 3*d*F*E per layer
+# times the layer count reproduces the parameter totals the paper prints.  Synthetic weights.
+CONFIGS["phi"] = LayerConfig("phi", T=4096, d=4096, E=16, k=2, F=6400, dtype=BF16, renorm=1,
+                             seed=6006, x_std=1.0, w_std=-1.0)
+CONFIGS["llama4"] = LayerConfig("llama4", T=4096, d=5120, E=16, k=1, F=8192, dtype=BF16, renorm=0,
+                                seed=7007, x_std=1.0, w_std=-1.0)
 # The skewed layer with its last four experts forced empty.
 CONFIGS["skew_empty"] = replace(CONFIGS["skew"], name="skew_empty", empty_tail=4)
 

@@ -103,7 +103,7 @@ def check_sampled_outputs(cfg, L, buf, ridx, rw, rd, n_tokens, seed=0):
 
 
 @pytest.mark.parametrize("name,n_tokens", [("mixtral", 40), ("finegrained", 48), ("skew", 48),
-                                           ("skew_empty", 24)])
+                                           ("skew_empty", 24), ("phi", 24), ("llama4", 16)])
 def test_full_size_sampled(name, n_tokens):
     cfg = si.CONFIGS[name]
     print(f"workload {name}: generating", flush=True)

@@ -316,6 +316,16 @@ def test_paper_shape_facts(repo_root):
     assert (cfg.k, cfg.E) == tuple(int(v) for v in facts["mixtral_active_total"].split("/"))
     # largest gate/predictor = 80 K parameters = a bias-free d x E linear map (5120 x 16)
     assert abs(5120 * 16 - float(facts["largest_gate_params"])) / 81920 < 0.03
+    # the other two models of Table 1: widths come from the public model configurations; the
+    # experts (three d x F matrices each) must account for most of the printed parameter totals
+    for name, layers, total in (("phi", "phi_layers", "phi_params_total_b"),
+                                ("llama4", "llama4_layers", "llama4_params_total_b")):
+        c = si.CONFIGS[name]
+        experts = 3 * c.d * c.F * c.E * int(facts[layers]) / 1e9
+        assert 0.85 * float(facts[total]) <= experts <= float(facts[total])
+    assert (si.CONFIGS["phi"].k, si.CONFIGS["phi"].E) == tuple(int(v) for v in facts["phi_active_total"].split("/"))
+    assert (si.CONFIGS["llama4"].k, si.CONFIGS["llama4"].E) == tuple(
+        int(v) for v in facts["llama4_active_total"].split("/"))
 
 
 # ----------------------------------------------------------------------------- planted mistakes
