@@ -316,27 +316,19 @@ extern "C" int moe_count_and_permute(const moe_shape_t* shape, const void* x,
     hipLaunchKernelGGL(moe::rank_small_kernel, dim3(1), dim3(256), 0, st, topk_idx, T * k, E, counts,
                        offsets, dst_row, src_assign);
   } else if (nth == 256) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(moe::rank_kernel<256>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              128 * 256 * 2 + 128 * 8) != hipSuccess)
-        return MOE_ERR_HIP;
-      attr_set = true;
-    }
+    static moe::LdsOnce once;
+    if (moe::ensure_dynamic_lds(once, reinterpret_cast<const void*>(moe::rank_kernel<256>),
+                                128 * 256 * 2 + 128 * 8) != MOE_OK)
+      return MOE_ERR_HIP;
     hipLaunchKernelGGL(moe::hist_kernel<256>, dim3(grid), dim3(256), 0, st, topk_idx, T, k, E,
                        partial);
     hipLaunchKernelGGL(moe::rank_kernel<256>, dim3(grid), dim3(256), lds, st, topk_idx, T, k, E,
                        partial, grid, counts, offsets, dst_row, src_assign);
   } else {
-    static bool attr_set = false;
-    if (!attr_set) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void*>(moe::rank_kernel<128>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              256 * 128 * 2 + 256 * 8) != hipSuccess)
-        return MOE_ERR_HIP;
-      attr_set = true;
-    }
+    static moe::LdsOnce once;
+    if (moe::ensure_dynamic_lds(once, reinterpret_cast<const void*>(moe::rank_kernel<128>),
+                                256 * 128 * 2 + 256 * 8) != MOE_OK)
+      return MOE_ERR_HIP;
     hipLaunchKernelGGL(moe::hist_kernel<128>, dim3(grid), dim3(128), 0, st, topk_idx, T, k, E,
                        partial);
     hipLaunchKernelGGL(moe::rank_kernel<128>, dim3(grid), dim3(128), lds, st, topk_idx, T, k, E,

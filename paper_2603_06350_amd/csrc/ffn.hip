@@ -596,13 +596,10 @@ static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 static int launch_mfma(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t st) {
   constexpr int lds_bytes = NSTAGE * (BM + BROWS) * ROWB;
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
-      return MOE_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOnce once;
+  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>),
+                         lds_bytes) != MOE_OK)
+    return MOE_ERR_HIP;
   a.mode = mode;
   a.bm_main = bm_main;
   int64_t grid = max_m_tiles(A, a.E, bm_main, mode) * a.n_tiles;
@@ -655,13 +652,12 @@ struct SideStream {
   hipEvent_t fork = nullptr, join = nullptr;
   bool ready = false;
 };
-constexpr int MAX_DEVICES = 64;
-static SideStream g_side[MAX_DEVICES];
+static SideStream g_side[MOE_MAX_DEVICES];
 static std::mutex g_side_mutex;   // also serialises fork ... join sequences that share the events
 
 static SideStream* side_stream_locked() {
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MOE_MAX_DEVICES) return nullptr;
   SideStream& s = g_side[dev];
   if (!s.ready) {
     if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;

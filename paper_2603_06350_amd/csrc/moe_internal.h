@@ -36,6 +36,23 @@ inline int check_shape(const moe_shape_t* s) {
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
 
+// Raises a kernel's dynamic-LDS limit once per device.  `done` is the caller's per-kernel flag
+// array (one static array per kernel); setting the attribute twice is harmless, so a race between
+// two first calls needs no lock.
+constexpr int MOE_MAX_DEVICES = 64;
+struct LdsOnce {
+  bool done[MOE_MAX_DEVICES] = {};
+};
+inline int ensure_dynamic_lds(LdsOnce& once, const void* kernel, int bytes) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MOE_MAX_DEVICES) return MOE_ERR_HIP;
+  if (once.done[dev]) return MOE_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return MOE_ERR_HIP;
+  once.done[dev] = true;
+  return MOE_OK;
+}
+
 // ---- device helpers -------------------------------------------------------------------------
 typedef uint16_t bf16_t;  // bfloat16 bit pattern
 

@@ -457,14 +457,10 @@ static size_t route_lds_bytes(int E) {
 template <bool BF16, int NT, int RPW>
 static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
                             int32_t* idx, float* w, float* scores, int tpb, hipStream_t st) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(route_lds_bytes(MOE_MAX_E))) != hipSuccess)
-      return MOE_ERR_HIP;
-    attr_set = true;
-  }
+  static LdsOnce once;
+  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW>),
+                         static_cast<int>(route_lds_bytes(MOE_MAX_E))) != MOE_OK)
+    return MOE_ERR_HIP;
   const int grid = (s->T + tpb - 1) / tpb;
   hipLaunchKernelGGL((route_kernel<BF16, NT, RPW>), dim3(grid), dim3(RT_THREADS),
                      route_lds_bytes(s->E), st, static_cast<const uint4*>(x),
