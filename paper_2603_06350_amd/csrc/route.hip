@@ -399,7 +399,8 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       if (lane == 0) flag[row] = amb;
     }
   } else {
-    if (threadIdx.x < tpb) flag[threadIdx.x] = (t0 + threadIdx.x < T) ? RT_CMAX + 1 : 0;
+    const int tid = static_cast<int>(threadIdx.x);
+    if (tid < tpb) flag[tid] = (t0 + tid < T) ? RT_CMAX + 1 : 0;
   }
   __syncthreads();
   // ---- exact pass for the tokens that need it (block-uniform control flow) -------------------
