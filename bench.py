@@ -263,8 +263,8 @@ def main():
                 "cache holds, so the HBM-bound calls start cold; event timings include launch gaps",
     }
     out = {
-        "metric": "MoE-layer tokens/sec (Mixtral shape)" if cfg.name == "mixtral"
-        else f"MoE-layer tokens/sec ({cfg.name})",
+        "metric": "MoE-layer tokens/sec + grouped-FFN % of bf16 MFMA peak (Mixtral shape)"
+        if cfg.name == "mixtral" else f"MoE-layer tokens/sec + grouped-FFN % of bf16 MFMA peak ({cfg.name})",
         "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -273,6 +273,7 @@ def main():
                                f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward",
                    "ffn_input": "x through the permutation map (moe_grouped_ffn_gather)" if fused
                    else "materialised x_perm (moe_grouped_ffn)"},
+        "ffn_pct_of_bf16_mfma_peak": 100.0 * others["ffn_total_frac_of_mfma_peak"],
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
         "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,
     }
