@@ -157,8 +157,10 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   return tc.m_begin < tc.m_end;
 }
 
+// silu(g) * u with the hardware exponential and reciprocal (about 1 ulp each; the result is
+// rounded to bf16 right after)
 __device__ __forceinline__ float silu_mul(float g, float u) {
-  return g * u * __frcp_rn(1.0f + __expf(-g));
+  return g * u * __builtin_amdgcn_rcpf(1.0f + __expf(-g));
 }
 
 // --------------------------------------------------------------------------------------------
