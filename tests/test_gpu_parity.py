@@ -427,3 +427,44 @@ def test_ffn_gather_rejects_missing_map_and_survives_bad_entries():
                              buf.y_perm)
     torch.cuda.synchronize()
     assert np.isfinite(orc.to_f64(host(buf.y_perm))).all()
+
+
+def test_two_host_threads_on_two_streams():
+    """The header promises that calls from several host threads are safe (the grouped FFN shares one
+    side stream and event pair per device under a mutex).  Two threads, each with its own stream
+    and buffers, run the layer repeatedly at the same time; every result equals the one obtained
+    alone."""
+    import threading
+    cfgs = [si.small_config("thr_a", T=1400, d=128, E=2, k=2, F=256),
+            si.small_config("thr_b", T=900, d=256, E=4, k=2, F=128, seed=11)]
+    jobs = []
+    for cfg in cfgs:
+        L = si.make_layer(cfg)
+        args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+        buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+        buf.forward(*args)
+        torch.cuda.synchronize()
+        jobs.append((cfg, args, buf, host(buf.y).copy(), torch.cuda.Stream()))
+    errors = []
+
+    def run(job):
+        cfg, args, buf, want, stream = job
+        try:
+            for it in range(20):
+                with torch.cuda.stream(stream):
+                    buf.y.zero_()
+                    buf.forward(*args, stream=stream, gather_in_ffn=bool(it & 1))
+                stream.synchronize()
+                if not np.array_equal(host(buf.y), want):
+                    errors.append(f"{cfg.name}: iteration {it} differs")
+                    return
+        except Exception as exc:  # noqa: BLE001
+            errors.append(f"{cfg.name}: {exc!r}")
+
+    threads = [threading.Thread(target=run, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a thread did not finish"
+    assert not errors, errors
