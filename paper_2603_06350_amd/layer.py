@@ -125,7 +125,7 @@ class LoadPredictor:
                                self.seg_offsets, self.seg_expert, self.n_segments, s)
         if self.n_gpus > 0:
             cur, prev = self.round & 1, (self.round & 1) ^ 1
-            with torch.cuda.stream(s):          # keep this round's counts for the next round's warm set
+            with torch.cuda.stream(s):          # keep these replica counts: the next call's warm set
                 self.placed_replicas[cur].copy_(self.replicas, non_blocking=True)
             B.moe_place_replicas(self.E, self.counts, self.replicas, self.n_gpus,
                                  self.placed_replicas[prev] if self.round > 0 else None,
