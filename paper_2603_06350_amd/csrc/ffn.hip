@@ -365,7 +365,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
     // The stage's one barrier sits between its two k-steps.  Before it a wave waits for its own
     // global->LDS loads of stage kt+1 and for its last LDS reads of buffer CUR; after it, buffer
     // CUR^1 may be read (first fragments of stage kt+1, fetched while k-step 1 multiplies) and
-    // buffer CUR may be overwritten (loads of stage kt+2, one per MFMA group).  Inline asm pins
+    // buffer CUR may be overwritten (loads of stage kt+2, issued at once).  Inline asm pins
     // the order; the compiler does not see these LDS reads, so it inserts no waits of its own.
     int xad[2][KSTEPS], wad[2][KSTEPS];       // per stage buffer, per k-step LDS byte addresses
 #pragma unroll
@@ -402,6 +402,12 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
+      // Buffer CUR is free: the loads of stage kt+2 go out at once (they have exactly one stage
+      // to land, and every cycle earlier counts).
+      if (more2) {
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i) issue_load(i, kt + 2, CUR);
+      }
       // k-step 1 multiplies (wf, xB): all it needs has landed.  The fragment reads below fetch
       // the first k-step of stage kt+1; after the last stage they read stale LDS and go unused.
       read_x(xA, xad[CUR ^ 1][0]);
@@ -410,11 +416,6 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xB[mi]);
         MOE_RD(wf[ni], wad[CUR ^ 1][0], MOE_W_OFF(ni));
-        if (more2) {
-#pragma unroll
-          for (int i = 0; i < NLOAD; ++i)
-            if (i % NI == ni) issue_load(i, kt + 2, CUR);
-        }
       }
     };
     using T0 = std::integral_constant<int, 0>;
