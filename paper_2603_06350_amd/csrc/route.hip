@@ -449,6 +449,470 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   }
 }
 
+// ================================================================================================
+// Large-batch bf16 path.  The kernel above gives every 16-token tile a block of its own and lets
+// each of its waves fetch its own w_gate fragments: per token that moves E*d/16 elements of w_gate
+// through the L2, four times the bytes of x itself at 64 experts, and it spends one wave per token
+// on the selection.  Here a block takes TILES tiles (16*TILES tokens) and its eight waves are
+// TILES x KS (tile, slice of the hidden dimension); w_gate goes through LDS once per block (a ring
+// of 64-element stages filled by direct-to-LDS loads), x goes straight from HBM into MFMA
+// fragments.  The partial score tiles meet in LDS and are read back in a layout made for the
+// selection: every wave takes 2 TILES of the block's tokens, 64 / (2 TILES) adjacent lanes per
+// token, each lane a contiguous range of experts.  A lane finds its best remaining score by a
+// tournament over its registers, the lanes of a token merge by DPP butterflies, so one pick
+// costs a few dozen instructions for all the wave's tokens together.  Ambiguous tokens follow the
+// same protocol as above (exact re-scoring of the listed candidates by the whole block, four
+// tokens per pass), after which their lanes patch the scores they hold and select once more.
+constexpr int RT_KSEL = 16;      // largest k this path handles (the picks of a tile sit in LDS)
+constexpr int RT_NSTAGE = 3;     // LDS ring of w_gate stages
+
+__device__ __forceinline__ int rt_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+template <int N> __device__ __forceinline__ void rt_wait_vmcnt() {
+  static_assert(N >= 0 && N <= 8, "vmcnt immediate");
+#define MOE_RT_VMCNT_CASE(n) \
+  if constexpr (N == n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory");
+  MOE_RT_VMCNT_CASE(0) MOE_RT_VMCNT_CASE(1) MOE_RT_VMCNT_CASE(2) MOE_RT_VMCNT_CASE(3)
+  MOE_RT_VMCNT_CASE(4) MOE_RT_VMCNT_CASE(5) MOE_RT_VMCNT_CASE(6) MOE_RT_VMCNT_CASE(7)
+  MOE_RT_VMCNT_CASE(8)
+#undef MOE_RT_VMCNT_CASE
+}
+
+// Butterfly exchange inside groups of 4, 8 or 16 adjacent lanes by DPP (lane swaps in quads, then
+// the half-row and row mirrors): after level l every lane has seen 2^(l+1) lanes of its group.
+template <int CTRL> __device__ __forceinline__ float rt_dpp(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ int rt_dpp(int x) {
+  return __builtin_amdgcn_update_dpp(x, x, CTRL, 0xF, 0xF, false);
+}
+#define MOE_RT_GROUP_LEVELS(LPT, STEP)      \
+  STEP(0xB1) STEP(0x4E)                     \
+  if constexpr ((LPT) >= 8) { STEP(0x141) } \
+  if constexpr ((LPT) >= 16) { STEP(0x140) }
+
+template <int LPT> __device__ __forceinline__ float group_sum(float x) {
+#define MOE_RT_STEP(c) x += rt_dpp<c>(x);
+  MOE_RT_GROUP_LEVELS(LPT, MOE_RT_STEP)
+#undef MOE_RT_STEP
+  return x;
+}
+template <int LPT> __device__ __forceinline__ int group_sum(int x) {
+#define MOE_RT_STEP(c) x += rt_dpp<c>(x);
+  MOE_RT_GROUP_LEVELS(LPT, MOE_RT_STEP)
+#undef MOE_RT_STEP
+  return x;
+}
+template <int LPT> __device__ __forceinline__ float group_max(float x) {
+#define MOE_RT_STEP(c) x = fmaxf(x, rt_dpp<c>(x));
+  MOE_RT_GROUP_LEVELS(LPT, MOE_RT_STEP)
+#undef MOE_RT_STEP
+  return x;
+}
+
+// Selection for the 64 / LPT tokens of a wave.  A token belongs to LPT adjacent lanes; lane j of the
+// group holds the scores s[q] of experts j S + q (anything for experts >= E: never looked at).
+// picks: this wave's LDS scratch, float pw[RT_KSEL + 1][16] followed by int pe[RT_KSEL + 1][16],
+// indexed by the token's number in the wave.  With `check`, a token whose choice is within the fast
+// pass's error margin writes nothing; it lists its candidates in cand_row[RT_CMAX] (order
+// arbitrary; *ccount_row must be zero) and appends one (row | position << 16) per candidate to
+// plist, or, if there are more than RT_CMAX, its row to flist (re-score all experts).
+// `commit`: this lane's token exists and writes its outputs (if it is not flagged).
+// Every lane of the wave must call this (it exchanges data between lanes).
+template <int S, int LPT>
+__device__ void select_tile(const float (&s)[S], float lmax, bool check, bool commit, int E, int k,
+                            int renorm, int64_t t, int row, float* __restrict__ picks,
+                            int* __restrict__ cand_row, int* __restrict__ ccount_row,
+                            int* __restrict__ plist, int* __restrict__ pcount,
+                            int* __restrict__ flist, int* __restrict__ fcount,
+                            int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                            float* __restrict__ scores_out) {
+  const int lane = lane_id();
+  const int tl = lane / LPT, j = lane % LPT;
+  const int e0 = j * S;
+  float* pv = picks;
+  int* pe = reinterpret_cast<int*>(picks + (RT_KSEL + 1) * 16);
+  unsigned taken = 0u;                         // bit q: that expert is picked or does not exist
+  float wv[S];                                 // the scores still to pick from (-inf once taken)
+#pragma unroll
+  for (int q = 0; q < S; ++q) {
+    const bool exists = e0 + q < E;
+    if (!exists) taken |= 1u << q;
+    wv[q] = exists ? s[q] : -INFINITY;
+  }
+  // softmax over all experts: partial sums per lane, the lanes of a token added as a butterfly
+  // (every lane gets the same bits: each level adds the same two numbers on both sides)
+  float top = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < S; ++q) top = fmaxf(top, wv[q]);
+  top = group_max<LPT>(top);
+  float psum = 0.f;
+#pragma unroll
+  for (int q = 0; q < S; ++q)
+    if (e0 + q < E) psum += expf(s[q] - top);
+  const float denom = group_sum<LPT>(psum);
+  float ws = 0.f;                              // sum of the chosen experts' probabilities
+  const int npick = E > k ? k + 1 : k;
+  float prev = INFINITY, gap_prev = INFINITY;
+  bool amb = false;
+  for (int i = 0; i < npick; ++i) {
+    // best remaining score of this lane by a tournament: the right entry wins only if strictly
+    // greater, so equal scores keep the lowest index
+    float tv[S];
+    int tq[S];
+#pragma unroll
+    for (int q = 0; q < S; ++q) {
+      tv[q] = wv[q];
+      tq[q] = q;
+    }
+#pragma unroll
+    for (int w = 1; w < S; w <<= 1)
+#pragma unroll
+      for (int m = 0; m + w < S; m += 2 * w) {
+        const bool r = tv[m + w] > tv[m];
+        tv[m] = r ? tv[m + w] : tv[m];
+        tq[m] = r ? tq[m + w] : tq[m];
+      }
+    float bv = tv[0];
+    int be = e0 + tq[0];
+    if ((taken >> tq[0]) & 1u) {
+      // nothing is left in this lane, or only scores of -inf: the first free entry, if any
+      be = 0x7FFFFFFF;
+#pragma unroll
+      for (int q = S - 1; q >= 0; --q)
+        if (!((taken >> q) & 1u)) be = e0 + q;
+    }
+    // merge over the lanes of the token: larger score, then lower index ("nothing" is
+    // (-inf, INT_MAX) and loses against everything)
+#define MOE_RT_STEP(c)                                              \
+  {                                                                 \
+    const float ov = rt_dpp<c>(bv);                                 \
+    const int oe = rt_dpp<c>(be);                                   \
+    const bool take = ov > bv || (ov == bv && oe < be);             \
+    bv = take ? ov : bv;                                            \
+    be = take ? oe : be;                                            \
+  }
+    MOE_RT_GROUP_LEVELS(LPT, MOE_RT_STEP)
+#undef MOE_RT_STEP
+    {
+      const int qs = be - e0;                  // in [0, S) only in the lane that holds the winner
+      if (qs >= 0 && qs < S) taken |= 1u << qs;
+#pragma unroll
+      for (int q = 0; q < S; ++q) wv[q] = q == qs ? -INFINITY : wv[q];
+    }
+    const float pw = expf(bv - top) / denom;
+    if (i < k) ws += pw;
+    if (j == 0) {
+      pv[i * 16 + tl] = pw;
+      pe[i * 16 + tl] = be;
+    }
+    if (i >= 1) {
+      // pick i-1 is a chosen one: its neighbours are picks i-2 and i
+      const float gap = prev - bv;
+      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+      amb = amb || !(fminf(gap_prev, gap) > tol);
+      gap_prev = gap;
+    }
+    prev = bv;
+  }
+  if (npick == k) {                            // E == k: the last chosen score has no lower neighbour
+    const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+    amb = amb || !(gap_prev > tol);
+  }
+  amb = amb && check;
+  // candidates of a flagged token: every expert not clearly below the last pick
+  const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev));
+  int n_local = 0;
+  if (amb) {
+#pragma unroll
+    for (int q = 0; q < S; ++q)
+      if (e0 + q < E && s[q] >= prev - margin) ++n_local;
+  }
+  const int n_all = group_sum<LPT>(n_local);
+  if (amb && commit) {
+    if (n_all <= RT_CMAX) {
+#pragma unroll
+      for (int q = 0; q < S; ++q)
+        if (e0 + q < E && s[q] >= prev - margin) {
+          const int pos = atomicAdd(ccount_row, 1);
+          cand_row[pos] = e0 + q;
+          plist[atomicAdd(pcount, 1)] = row | (pos << 16);
+        }
+    } else if (j == 0) {
+      flist[atomicAdd(fcount, 1)] = row;
+    }
+  }
+  if (amb || !commit) return;
+  for (int i = j; i < k; i += LPT) {
+    const float p = pv[i * 16 + tl];
+    topk_idx[t * k + i] = pe[i * 16 + tl];
+    topk_w[t * k + i] = renorm ? p / ws : p;
+  }
+  if (scores_out) {
+#pragma unroll
+    for (int q = 0; q < S; ++q)
+      if (e0 + q < E) scores_out[t * E + e0 + q] = s[q];
+  }
+}
+
+// Exact gate sums (fp64) of up to RT_CMAX (token, candidate expert) pairs, this wave's part of the
+// hidden dimension: the arithmetic of exact_candidates with a token of its own per candidate
+// slot.  pairs[] holds (row | position in the token's candidate list << 16).
+// Result: dpart[wave * RT_CMAX + pair].
+__device__ void exact_pairs(const uint4* __restrict__ x, const uint4* __restrict__ wg, int row16,
+                            int64_t t0, const int* __restrict__ pairs, int npairs,
+                            const int* __restrict__ cand_all, int wave, double* __restrict__ dpart) {
+  const int lane = lane_id();
+  const int c = lane & (RT_CMAX - 1);
+  const int sub = lane / RT_CMAX;
+  constexpr int NSUB = MOE_WAVE / RT_CMAX;
+  const int entry = pairs[c < npairs ? c : 0];
+  const int prow = entry & 0xFFFF, pos = entry >> 16;
+  const int e = cand_all[prow * RT_CMAX + pos];
+  const uint4* xrow = x + (t0 + prow) * row16;
+  const uint4* wrow = wg + static_cast<int64_t>(e) * row16;
+  const int cw = (row16 + RT_NW - 1) / RT_NW;
+  const int c0 = wave * cw;
+  const int c1 = min(row16, c0 + cw);
+  double acc = 0.0;
+  constexpr int XB = 8;
+  for (int cb = c0 + sub; cb < c1; cb += XB * NSUB) {
+    uint4 av[XB], bv[XB];
+#pragma unroll
+    for (int u = 0; u < XB; ++u) {
+      const int cc = min(cb + u * NSUB, row16 - 1);
+      av[u] = xrow[cc];
+      bv[u] = wrow[cc];
+    }
+#pragma unroll
+    for (int u = 0; u < XB; ++u) {
+      if (cb + u * NSUB < c1) {
+        const uint4 a = av[u];
+        const uint4 b = bv[u];
+        acc = fma(static_cast<double>(bf16lo(a.x)), static_cast<double>(bf16lo(b.x)), acc);
+        acc = fma(static_cast<double>(bf16hi(a.x)), static_cast<double>(bf16hi(b.x)), acc);
+        acc = fma(static_cast<double>(bf16lo(a.y)), static_cast<double>(bf16lo(b.y)), acc);
+        acc = fma(static_cast<double>(bf16hi(a.y)), static_cast<double>(bf16hi(b.y)), acc);
+        acc = fma(static_cast<double>(bf16lo(a.z)), static_cast<double>(bf16lo(b.z)), acc);
+        acc = fma(static_cast<double>(bf16hi(a.z)), static_cast<double>(bf16hi(b.z)), acc);
+        acc = fma(static_cast<double>(bf16lo(a.w)), static_cast<double>(bf16lo(b.w)), acc);
+        acc = fma(static_cast<double>(bf16hi(a.w)), static_cast<double>(bf16hi(b.w)), acc);
+      }
+    }
+  }
+  acc += __shfl_xor(acc, 16);
+  acc += __shfl_xor(acc, 32);
+  if (sub == 0 && c < npairs) dpart[wave * RT_CMAX + c] = acc;
+}
+
+template <int NT, int TILES>
+struct RouteTileLds {
+  static constexpr int KS = RT_NW / TILES;
+  static constexpr int ROWS = KS * NT * 16;                 // w_gate rows (expert, slice) per stage
+  static constexpr int STAGE = ROWS * 128;
+  static constexpr int PART = RT_NW * NT * 4 * MOE_WAVE * 4;                // aliases the stages
+  static constexpr int RING = RT_NSTAGE * STAGE > PART ? RT_NSTAGE * STAGE : PART;
+  static constexpr int PICKS = RING;                        // float/int [RT_NW][2][RT_KSEL + 1][16]
+  static constexpr int CAND = PICKS + RT_NW * 2 * (RT_KSEL + 1) * 16 * 4;   // int [16 TILES][RT_CMAX]
+  static constexpr int CCOUNT = CAND + TILES * 16 * RT_CMAX * 4;            // int [16 TILES]
+  static constexpr int PLIST = CCOUNT + TILES * 16 * 4;                     // int [16 TILES][RT_CMAX]
+  static constexpr int FLIST = PLIST + TILES * 16 * RT_CMAX * 4;            // int [16 TILES] + two counts
+  static constexpr int DPART = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;   // double [RT_NW][max(E, RT_CMAX)]
+  static constexpr int TOTAL = DPART + RT_NW * (NT * 16 > RT_CMAX ? NT * 16 : RT_CMAX) * 8;
+};
+
+// Requires d % (64 KS) == 0 and k <= RT_KSEL (the host checks).
+// Four waves per SIMD (two blocks per CU, 128 registers) wherever the LDS use allows two blocks.
+template <int NT, int TILES>
+__global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 * 1024 ? 4 : 2)) void route_tile_kernel(
+    const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
+    int d, int E, int k, int renorm, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    float* __restrict__ scores_out) {
+  using L = RouteTileLds<NT, TILES>;
+  constexpr int KS = L::KS;
+  constexpr int QE = NT >= 4 ? NT / 4 : 1;
+  constexpr int NLB = (L::ROWS / 8 + RT_NW - 1) / RT_NW;    // w_gate load instructions per wave per stage
+  constexpr int NL = NLB + 2;                               // ... plus the two x fragments
+  extern __shared__ __align__(1024) unsigned char smem[];
+  float* part = reinterpret_cast<float*>(smem);
+  int* cand_all = reinterpret_cast<int*>(smem + L::CAND);
+  int* ccount = reinterpret_cast<int*>(smem + L::CCOUNT);
+  int* plist = reinterpret_cast<int*>(smem + L::PLIST);
+  int* flist = reinterpret_cast<int*>(smem + L::FLIST);
+  int* fcount = flist + TILES * 16;
+  int* pcount = fcount + 1;
+  double* dpart = reinterpret_cast<double*>(smem + L::DPART);
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
+  const int ks = wave / TILES, tile = wave % TILES;        // waves 0..TILES-1 (ks = 0) own the tiles
+  const int t0 = blockIdx.x * (16 * TILES);
+  const int row16 = d / 8;
+  const int tok = lane & 15, g = lane >> 4;
+  const int kgrp = ((lane >> 4) & 1) * 2 + (lane >> 5);     // which 16-byte chunk of a k-step's four
+  const int cs = row16 / KS;                                // chunks per slice, a multiple of 8
+  const int KT = cs / 8;                                    // 64-element stages per slice
+  if (threadIdx.x == 0) *fcount = *pcount = 0;
+
+  // ---- w_gate -> LDS: instruction j of this wave fills rows 8 i .. 8 i + 7 of the stage, i = (8 j + wave)
+  //      modulo the number of row groups (small stages are loaded twice with the same bytes, so
+  //      that every wave issues the same number of loads and one wait count serves all).
+  //      Stage row r = slice * (16 NT) + expert; experts past E re-read expert E - 1.
+  const __amdgpu_buffer_rsrc_t rs_w = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint4*>(wg), 0, 0x7FFFFFFF, 0x00020000);
+  uint32_t woff[NLB], wlds[NLB];
+#pragma unroll
+  for (int j = 0; j < NLB; ++j) {
+    const int i = (j * RT_NW + wave) % (L::ROWS / 8);
+    const int r = i * 8 + (lane >> 3);
+    const int e = min(r % (NT * 16), E - 1), sl = r / (NT * 16);
+    const int chunk = (lane & 7) ^ rt_swz(r);
+    woff[j] = (static_cast<uint32_t>(e) * row16 + sl * cs + chunk) * 16u;
+    wlds[j] = i * 1024;
+  }
+  // ---- x -> registers: lane (tok, kgrp) of k-step j of stage kt holds chunk 8 kt + 4 j + kgrp
+  const int t_ld = min(t0 + tile * 16 + tok, T - 1);
+  const uint4* xrow = x + static_cast<int64_t>(t_ld) * row16 + ks * cs + kgrp;
+  uint4 a[RT_NSTAGE][2];
+  auto issue = [&](int kt, auto slot_c) {
+    constexpr int SLOT = decltype(slot_c)::value;
+#pragma unroll
+    for (int j = 0; j < NLB; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rs_w, (__attribute__((address_space(3))) void*)(smem + SLOT * L::STAGE + wlds[j]), 16,
+          static_cast<int>(woff[j]), kt * 128, 0, 0);
+    a[SLOT][0] = xrow[kt * 8];
+    a[SLOT][1] = xrow[kt * 8 + 4];
+  };
+  // LDS read address of the w_gate fragment: row = own slice, expert 16 nt + lane % 16
+  const int f = rt_swz(tok);
+  const int wrd = (ks * NT * 16 + tok) * 128;
+  int koff[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) koff[j] = ((j * 4 + kgrp) ^ f) << 4;
+
+  f32x4_t acc[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+  using std::integral_constant;
+  issue(0, integral_constant<int, 0>{});
+  if (KT > 1) issue(1, integral_constant<int, 1>{});
+  auto stage = [&](int kt, auto slot_c) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    if (kt + 1 < KT) rt_wait_vmcnt<NL>(); else rt_wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();       // stage kt landed for all waves; the slot of kt - 1 is free
+    asm volatile("" ::: "memory");
+    if (kt + 2 < KT) issue(kt + 2, integral_constant<int, (SLOT + 2) % RT_NSTAGE>{});
+    const unsigned char* sb = smem + SLOT * L::STAGE + wrd;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const bf16x8_t xf = __builtin_bit_cast(bf16x8_t, a[SLOT][j]);
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const bf16x8_t wf = *reinterpret_cast<const bf16x8_t*>(sb + nt * 16 * 128 + koff[j]);
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nt], 0, 0, 0);
+      }
+    }
+  };
+  int kt = 0;
+  for (; kt + 2 < KT; kt += 3) {
+    stage(kt, integral_constant<int, 0>{});
+    stage(kt + 1, integral_constant<int, 1>{});
+    stage(kt + 2, integral_constant<int, 2>{});
+  }
+  if (kt < KT) stage(kt, integral_constant<int, 0>{});
+  if (kt + 1 < KT) stage(kt + 1, integral_constant<int, 1>{});
+
+  // ---- the partial score tiles go through LDS and come back in the selection layout: wave
+  //      (ks, tile) takes tokens ks TPW .. ks TPW + TPW - 1 of its tile, LPT adjacent lanes per token,
+  //      lane j of a token the experts j S .. j S + S - 1; slices are added in slice order.
+  constexpr int LPT = 4 * KS, TPW = 16 / KS, S = 4 * NT / KS;
+  static_assert(S >= 1 && S * LPT == 16 * NT && TPW * LPT == MOE_WAVE, "selection layout");
+  __syncthreads();                      // the ring is no longer read
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) part[((wave * NT + nt) * 4 + v) * MOE_WAVE + lane] = acc[nt][v];
+  for (int i = threadIdx.x; i < TILES * 16; i += RT_THREADS) ccount[i] = 0;
+  __syncthreads();
+  const int tl = lane / LPT, j = lane % LPT;
+  const int trow = ks * TPW + tl;                           // token's row in its tile
+  const int row = tile * 16 + trow;                         // ... and in the block
+  const int64_t t = t0 + row;
+  const bool t_ok = t < T;
+  float s[S];
+  float la = 0.f;
+#pragma unroll
+  for (int q = 0; q < S; ++q) {
+    const int e = j * S + q;
+    const int at = (((e >> 4) * 4 + (e & 3)) * MOE_WAVE) + ((e >> 2) & 3) * 16 + trow;
+    float sum = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < KS; ++sl) sum += part[(sl * TILES + tile) * NT * 4 * MOE_WAVE + at];
+    if (e < E) {
+      la = fmaxf(la, fabsf(sum));
+      if (bias) sum += bias[e];
+    }
+    s[q] = sum;
+  }
+  la = group_max<LPT>(la);
+  float* picks = reinterpret_cast<float*>(smem + L::PICKS) + wave * 2 * (RT_KSEL + 1) * 16;
+  select_tile<S, LPT>(s, la, true, t_ok, E, k, renorm, t, row, picks, cand_all + row * RT_CMAX,
+                      ccount + row, plist, pcount, flist, fcount, topk_idx, topk_w, scores_out);
+  __syncthreads();
+  // ---- exact pass for the flagged tokens (block-uniform control flow) ----------------------------
+  bool redo = false;                    // this lane's token was flagged
+  const int np = *pcount;
+  for (int base = 0; base < np; base += RT_CMAX) {
+    // up to RT_CMAX (token, candidate) pairs share one pass over the hidden dimension
+    const int cnt = min(RT_CMAX, np - base);
+    exact_pairs(x, wg, row16, t0, plist + base, cnt, cand_all, wave, dpart);
+    __syncthreads();
+    for (int c = 0; c < cnt; ++c) {
+      const int prow = plist[base + c] & 0xFFFF;
+      if (prow == row) {
+        // the lanes of the token replace the score they hold by the exact one (fp64 sum of the
+        // eight slices in wave order, rounded once)
+        redo = true;
+        const int e = cand_all[prow * RT_CMAX + (plist[base + c] >> 16)];
+        double v64 = 0.0;
+#pragma unroll
+        for (int w = 0; w < RT_NW; ++w) v64 += dpart[w * RT_CMAX + c];
+        if (bias) v64 += static_cast<double>(bias[e]);
+#pragma unroll
+        for (int q = 0; q < S; ++q)
+          if (j * S + q == e) s[q] = static_cast<float>(v64);
+      }
+    }
+    __syncthreads();
+  }
+  const int nf = *fcount;
+  for (int fi = 0; fi < nf; ++fi) {
+    // too many candidates: all experts of this one token
+    const int frow = flist[fi];
+    exact_partial<true, QE>(x + static_cast<int64_t>(t0 + frow) * row16, wg, row16, E, wave, dpart);
+    __syncthreads();
+    if (frow == row) {
+      redo = true;
+#pragma unroll
+      for (int q = 0; q < S; ++q) {
+        const int e = j * S + q;
+        if (e < E) {
+          double v64 = 0.0;
+#pragma unroll
+          for (int w = 0; w < RT_NW; ++w) v64 += dpart[w * E + e];
+          if (bias) v64 += static_cast<double>(bias[e]);
+          s[q] = static_cast<float>(v64);
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (__ballot(redo) != 0ull)
+    select_tile<S, LPT>(s, 0.f, false, redo, E, k, renorm, t, row, picks, nullptr, nullptr, nullptr,
+                        nullptr, nullptr, nullptr, topk_idx, topk_w, scores_out);
+}
+
 static size_t route_lds_bytes(int E) {
   const size_t dn = E > RT_CMAX ? E : RT_CMAX;
   return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 +
@@ -483,6 +947,51 @@ static int launch_route(const moe_shape_t* s, const void* x, const void* wg, con
              : launch_route_rpw<BF16, NT, 1>(s, x, wg, bias, idx, w, scores, tpb, st);
 }
 
+template <int NT, int TILES>
+static int launch_route_tile(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
+                             int32_t* idx, float* w, float* scores, hipStream_t st) {
+  using L = RouteTileLds<NT, TILES>;
+  static LdsOnce once;
+  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(route_tile_kernel<NT, TILES>), L::TOTAL) != MOE_OK)
+    return MOE_ERR_HIP;
+  const int grid = (s->T + 16 * TILES - 1) / (16 * TILES);
+  hipLaunchKernelGGL((route_tile_kernel<NT, TILES>), dim3(grid), dim3(RT_THREADS), L::TOTAL, st,
+                     static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T, s->d, s->E,
+                     s->k, s->renorm, idx, w, scores);
+  return launch_status();
+}
+
+// The large-batch path takes over when the batch fills the chip with blocks of at least two tiles
+// (the most tiles per block that still leave every CU a block; the slices of the hidden dimension
+// must be whole 64-element stages) and k and E fit its selection; returns false otherwise.
+template <int NT>
+static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
+                           int32_t* idx, float* w, float* scores, hipStream_t st, int* rc) {
+  constexpr int MIN_GRID = 256;
+  if constexpr (NT > 4) {
+    return false;   // more than 64 experts: the per-lane tournament no longer fits the registers
+  } else {
+    if (s->k > RT_KSEL) return false;
+    for (int tiles = 8; tiles >= 2; tiles >>= 1) {
+      if ((s->T + 16 * tiles - 1) / (16 * tiles) < MIN_GRID) continue;
+      if (s->d % (64 * (RT_NW / tiles)) != 0) continue;
+      if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
+      if (tiles == 4) *rc = launch_route_tile<NT, 4>(s, x, wg, bias, idx, w, scores, st);
+      if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
+      return true;
+    }
+    return false;
+  }
+}
+
+template <int NT>
+static int launch_route_bf16(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
+                             int32_t* idx, float* w, float* scores, hipStream_t st) {
+  int rc = MOE_OK;
+  if (try_route_tile<NT>(s, x, wg, bias, idx, w, scores, st, &rc)) return rc;
+  return launch_route<true, NT>(s, x, wg, bias, idx, w, scores, st);
+}
+
 }  // namespace moe
 
 extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
@@ -496,11 +1005,11 @@ extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int E = shape->E;
   if (shape->dtype == MOE_BF16) {
-    if (E <= 16) return moe::launch_route<true, 1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 32) return moe::launch_route<true, 2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 64) return moe::launch_route<true, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 128) return moe::launch_route<true, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    return moe::launch_route<true, 16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    if (E <= 16) return moe::launch_route_bf16<1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    if (E <= 32) return moe::launch_route_bf16<2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    if (E <= 64) return moe::launch_route_bf16<4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    if (E <= 128) return moe::launch_route_bf16<8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    return moe::launch_route_bf16<16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
   }
   if (E <= 64) return moe::launch_route<false, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
   if (E <= 128) return moe::launch_route<false, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);

@@ -133,6 +133,71 @@ def test_route_near_ties_are_decided_like_the_oracle():
     check_route(cfg, L["x"], wg, bias)
 
 
+# Batches large enough for the large-batch routing kernel (at least 256 blocks of 2, 4 or 8 token
+# tiles; at most 64 experts, k <= 16, whole 64-element stages per slice of the hidden dimension).
+# The hidden size is small so that the oracle stays fast.  T is never a multiple of the block.
+BIG_ROUTE_CASES = [
+    dict(T=8195, d=256, E=64, k=6, renorm=1),      # 2 tiles per block, 4 slices
+    dict(T=8200, d=512, E=40, k=8, renorm=0),      # experts not a multiple of 16
+    dict(T=8193, d=256, E=5, k=5, renorm=1),       # k = E
+    dict(T=9000, d=768, E=16, k=16, renorm=0),     # the largest k this path takes, k = E
+    dict(T=16400, d=256, E=16, k=1, renorm=1),     # 4 tiles per block, 2 slices
+    dict(T=16390, d=384, E=33, k=3, renorm=1),
+    dict(T=32800, d=128, E=8, k=2, renorm=1),      # 8 tiles per block
+    dict(T=33000, d=64, E=64, k=15, renorm=0),     # one stage
+    dict(T=16400, d=192, E=8, k=2, renorm=1),      # slices would not be whole stages: per-tile kernel
+    dict(T=8195, d=256, E=32, k=17, renorm=1),     # k too large for it: per-tile kernel
+]
+
+
+@pytest.mark.parametrize("case", BIG_ROUTE_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}".format(**c))
+def test_route_large_batch_matches_oracle(case):
+    cfg = si.small_config(F=64, **case)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    check_route(cfg, L["x"], L["w_gate"], None)
+    bias = np.linspace(-1.5, 1.5, cfg.E).astype(np.float32)
+    check_route(cfg, L["x"], L["w_gate"], bias)
+
+
+@pytest.mark.parametrize("T", [8195, 16400, 32800])
+def test_route_large_batch_ties_and_near_ties(T):
+    # duplicated gate rows (exact ties), all-zero tokens (every score equal: more candidates than
+    # the exact pass lists, so all experts are re-scored), a 1e-6 bias between two equal rows
+    # (near-ties that only the exact pass resolves), experts masked by a huge negative bias
+    cfg = si.small_config(T=T, d=256, E=32, k=4, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    x, wg = L["x"].copy(), L["w_gate"].copy()
+    wg[9] = wg[2]
+    wg[13] = wg[2]
+    wg[30] = wg[17]
+    x[::7] = 0
+    idx, _ = check_route(cfg, x, wg, None)
+    assert np.array_equal(idx[::7], np.tile(np.arange(4, dtype=np.int32), (idx[::7].shape[0], 1)))
+    bias = np.zeros(32, dtype=np.float32)
+    bias[13] = 1e-6
+    bias[30] = -1e-6
+    _, _, rsc = orc.route(x, wg, 4, 1, bias)
+    m = orc.topk_margin(rsc, 4)
+    assert ((m < 1e-4) & (m > 0)).sum() > 5
+    check_route(cfg, x, wg, bias)
+    bias[20:] = -1e9
+    bias[3] = 1e9
+    idx, _ = check_route(cfg, x, wg, bias)
+    assert np.all(idx[:, 0] == 3) and idx.max() < 20
+
+
+def test_route_large_batch_without_scores_output():
+    cfg = si.small_config(T=8200, d=256, E=64, k=6, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    idx = torch.full((cfg.T, cfg.k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    B.moe_route(shape_of(cfg), dev(L["x"]), dev(L["w_gate"]), None, idx, w, None)
+    torch.cuda.synchronize()
+    ridx, rw, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm, None)
+    assert np.array_equal(host(idx), ridx)
+    assert np.all(np.abs(host(w) - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+
+
 # ----------------------------------------------------------------------------- count + permute
 def gpu_dispatch(cfg, x, idx):
     T, E, k, d = cfg.T, cfg.E, cfg.k, cfg.d
