@@ -968,16 +968,20 @@ template <int NT>
 static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
                            int32_t* idx, float* w, float* scores, hipStream_t st, int* rc) {
   constexpr int MIN_GRID = 256;
-  if constexpr (NT > 4) {
-    return false;   // more than 64 experts: the per-lane tournament no longer fits the registers
+  if constexpr (NT > 8) {
+    return false;   // more than 128 experts: a ring stage of w_gate no longer fits the LDS
   } else {
     if (s->k > RT_KSEL) return false;
-    for (int tiles = 8; tiles >= 2; tiles >>= 1) {
+    // 65 to 128 experts: only 4 tiles x 2 slices keeps both the stage and the per-lane tournament small
+    constexpr int TILES_MAX = NT > 4 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
+    for (int tiles = TILES_MAX; tiles >= TILES_MIN; tiles >>= 1) {
       if ((s->T + 16 * tiles - 1) / (16 * tiles) < MIN_GRID) continue;
       if (s->d % (64 * (RT_NW / tiles)) != 0) continue;
-      if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
+      if constexpr (NT <= 4) {
+        if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
+        if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
+      }
       if (tiles == 4) *rc = launch_route_tile<NT, 4>(s, x, wg, bias, idx, w, scores, st);
-      if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
       return true;
     }
     return false;

@@ -134,7 +134,7 @@ def test_route_near_ties_are_decided_like_the_oracle():
 
 
 # Batches large enough for the large-batch routing kernel (at least 256 blocks of 2, 4 or 8 token
-# tiles; at most 64 experts, k <= 16, whole 64-element stages per slice of the hidden dimension).
+# tiles, 4 only for 65 to 128 experts; k <= 16, whole 64-element stages per slice of the hidden dimension).
 # The hidden size is small so that the oracle stays fast.  T is never a multiple of the block.
 BIG_ROUTE_CASES = [
     dict(T=8195, d=256, E=64, k=6, renorm=1),      # 2 tiles per block, 4 slices
@@ -145,6 +145,9 @@ BIG_ROUTE_CASES = [
     dict(T=16390, d=384, E=33, k=3, renorm=1),
     dict(T=32800, d=128, E=8, k=2, renorm=1),      # 8 tiles per block
     dict(T=33000, d=64, E=64, k=15, renorm=0),     # one stage
+    dict(T=16400, d=256, E=128, k=8, renorm=1),    # more than 64 experts: 4 tiles per block only
+    dict(T=16390, d=128, E=100, k=6, renorm=0),
+    dict(T=16400, d=256, E=65, k=16, renorm=1),
     dict(T=16400, d=192, E=8, k=2, renorm=1),      # slices would not be whole stages: per-tile kernel
     dict(T=8195, d=256, E=32, k=17, renorm=1),     # k too large for it: per-tile kernel
 ]
@@ -159,12 +162,12 @@ def test_route_large_batch_matches_oracle(case):
     check_route(cfg, L["x"], L["w_gate"], bias)
 
 
-@pytest.mark.parametrize("T", [8195, 16400, 32800])
-def test_route_large_batch_ties_and_near_ties(T):
+@pytest.mark.parametrize("T,E", [(8195, 32), (16400, 32), (32800, 32), (16400, 128)])
+def test_route_large_batch_ties_and_near_ties(T, E):
     # duplicated gate rows (exact ties), all-zero tokens (every score equal: more candidates than
     # the exact pass lists, so all experts are re-scored), a 1e-6 bias between two equal rows
     # (near-ties that only the exact pass resolves), experts masked by a huge negative bias
-    cfg = si.small_config(T=T, d=256, E=32, k=4, F=64)
+    cfg = si.small_config(T=T, d=256, E=E, k=4, F=64)
     L = si.make_layer(cfg, parts=("x", "w_gate"))
     x, wg = L["x"].copy(), L["w_gate"].copy()
     wg[9] = wg[2]
@@ -173,7 +176,7 @@ def test_route_large_batch_ties_and_near_ties(T):
     x[::7] = 0
     idx, _ = check_route(cfg, x, wg, None)
     assert np.array_equal(idx[::7], np.tile(np.arange(4, dtype=np.int32), (idx[::7].shape[0], 1)))
-    bias = np.zeros(32, dtype=np.float32)
+    bias = np.zeros(E, dtype=np.float32)
     bias[13] = 1e-6
     bias[30] = -1e-6
     _, _, rsc = orc.route(x, wg, 4, 1, bias)
