@@ -122,7 +122,7 @@ def main():
             B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, part, st)
 
     def step():
-        B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
+        B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
         call_permute()
         call_ffn()
         B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
@@ -153,7 +153,7 @@ def main():
     for it in range(n_ev):
         e = evs[it]
         e[0].record(st)
-        B.moe_route(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, st)
+        B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
         e[1].record(st)
         call_permute()
         e[2].record(st)

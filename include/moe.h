@@ -57,12 +57,13 @@ typedef struct {
   int32_t renorm; /* 1: the k routing weights of a token are rescaled to sum to 1 */
 } moe_shape_t;
 
-/* Bytes of device workspace moe_count_and_permute needs for this shape. */
+/* Bytes of device workspace that moe_count_and_permute needs, and moe_route_ws can
+ * use, for this shape (one buffer of this size serves both calls of a layer). */
 int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes);
 
 /*
- * Gate + routing (Section 2.2: "the gating network routes tokens to specific
- * experts"; the gate is a bias-free d x E linear map, Sections 5 and 6.6).
+ * Gate + routing (Section 2.2: a gate decides, per token, which experts run it;
+ * the gate is a bias-free d x E linear map, Sections 5 and 6.6).
  *   score[t,e] = sum_i x[t,i] * w_gate[e,i]  (+ gate_bias[e] if given), as fp32
  *   topk_idx[t,:] = the k experts with the largest score, descending; equal
  *                   scores go to the lowest expert index
@@ -77,6 +78,19 @@ int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes);
 int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
               const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
               void* hip_stream);
+
+/*
+ * moe_route with a device workspace (same operation, same results).  For small
+ * batches (T <= 512) with a large gate matrix the gate product is then spread over
+ * the whole chip by a kernel of its own and the selection reads its scores from the
+ * workspace; without a workspace (and without scores_out) every block has to pull
+ * the whole gate matrix through one compute unit.  workspace: 16-byte aligned,
+ * contents ignored on entry and undefined on return; if it is NULL or smaller than
+ * moe_workspace_bytes() the call behaves like moe_route (no error).
+ */
+int moe_route_ws(const moe_shape_t* shape, const void* x, const void* w_gate,
+                 const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Expert load + dispatch (Section 4.1: the load of expert e is its token count;

@@ -17,7 +17,7 @@ _LIB_PATH = os.environ.get("MOE_GFX950_LIB") or os.path.join(
     os.path.dirname(os.path.abspath(__file__)), "libmoe_gfx950.so")
 _lib = None
 
-EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_count_and_permute", "moe_grouped_ffn",
+EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_route_ws", "moe_count_and_permute", "moe_grouped_ffn",
            "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
            "moe_grouped_ffn_gather_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
            "moe_place_replicas",
@@ -53,6 +53,7 @@ def load():
     shp = ctypes.POINTER(MoeShape)
     lib.moe_workspace_bytes.argtypes = [shp, ctypes.POINTER(ctypes.c_size_t)]
     lib.moe_route.argtypes = [shp, vp, vp, f32p, i32p, f32p, f32p, vp]
+    lib.moe_route_ws.argtypes = [shp, vp, vp, f32p, i32p, f32p, f32p, vp, ctypes.c_size_t, vp]
     lib.moe_count_and_permute.argtypes = [shp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp,
                                           ctypes.c_size_t, vp]
     lib.moe_grouped_ffn.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, vp]
@@ -115,6 +116,14 @@ def moe_route(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out=None, st
     _check("moe_route", load().moe_route(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias),
                                          _ptr(topk_idx), _ptr(topk_w), _ptr(scores_out),
                                          _stream(stream)))
+
+
+def moe_route_ws(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, workspace,
+                 workspace_bytes, stream=None):
+    _check("moe_route_ws",
+           load().moe_route_ws(ctypes.byref(shape), _ptr(x), _ptr(w_gate), _ptr(gate_bias),
+                               _ptr(topk_idx), _ptr(topk_w), _ptr(scores_out), _ptr(workspace),
+                               ctypes.c_size_t(int(workspace_bytes)), _stream(stream)))
 
 
 def moe_count_and_permute(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm,

@@ -33,29 +33,49 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4* __restrict__ 
   for (int u = 0; u < UNR; ++u)
 #pragma unroll
     for (int i = 0; i < NACC; ++i) acc[u][i] = 0.f;
-  for (int j = 0; j < k; ++j) {
-    const int src = __shfl(my_dst, j);
-    const float w = __shfl(my_w, j);
-    const uint4* in = y_perm + static_cast<int64_t>(src) * row16;
+  // The rows of JB experts are requested before the first is used (their addresses only depend
+  // on the map, and a wave that waits for one row at a time is latency-bound when there are few
+  // tokens); the sum still runs in ascending j.
+  constexpr int JB = 4;
+  for (int j0 = 0; j0 < k; j0 += JB) {
+    uint4 v[JB][UNR];
+    float w[JB];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const int c = c_begin + u * MOE_WAVE + lane;
-      if (c < row16) {
-        const uint4 v = in[c];
-        if (BF16) {
-          acc[u][0] = fmaf(w, bf16lo(v.x), acc[u][0]);
-          acc[u][1] = fmaf(w, bf16hi(v.x), acc[u][1]);
-          acc[u][2] = fmaf(w, bf16lo(v.y), acc[u][2]);
-          acc[u][3] = fmaf(w, bf16hi(v.y), acc[u][3]);
-          acc[u][4] = fmaf(w, bf16lo(v.z), acc[u][4]);
-          acc[u][5] = fmaf(w, bf16hi(v.z), acc[u][5]);
-          acc[u][6] = fmaf(w, bf16lo(v.w), acc[u][6]);
-          acc[u][7] = fmaf(w, bf16hi(v.w), acc[u][7]);
-        } else {
-          acc[u][0] = fmaf(w, __uint_as_float(v.x), acc[u][0]);
-          acc[u][1] = fmaf(w, __uint_as_float(v.y), acc[u][1]);
-          acc[u][2] = fmaf(w, __uint_as_float(v.z), acc[u][2]);
-          acc[u][3] = fmaf(w, __uint_as_float(v.w), acc[u][3]);
+    for (int jj = 0; jj < JB; ++jj) {
+      const int j = min(j0 + jj, k - 1);
+      const int src = __shfl(my_dst, j);
+      w[jj] = __shfl(my_w, j);
+      const uint4* in = y_perm + static_cast<int64_t>(src) * row16;
+      if (j0 + jj < k) {                            // wave-uniform
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+          const int c = c_begin + u * MOE_WAVE + lane;
+          v[jj][u] = in[min(c, row16 - 1)];
+        }
+      }
+    }
+#pragma unroll
+    for (int jj = 0; jj < JB; ++jj) {
+      if (j0 + jj < k) {
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+          const uint4 q = v[jj][u];
+          const float ww = w[jj];
+          if (BF16) {
+            acc[u][0] = fmaf(ww, bf16lo(q.x), acc[u][0]);
+            acc[u][1] = fmaf(ww, bf16hi(q.x), acc[u][1]);
+            acc[u][2] = fmaf(ww, bf16lo(q.y), acc[u][2]);
+            acc[u][3] = fmaf(ww, bf16hi(q.y), acc[u][3]);
+            acc[u][4] = fmaf(ww, bf16lo(q.z), acc[u][4]);
+            acc[u][5] = fmaf(ww, bf16hi(q.z), acc[u][5]);
+            acc[u][6] = fmaf(ww, bf16lo(q.w), acc[u][6]);
+            acc[u][7] = fmaf(ww, bf16hi(q.w), acc[u][7]);
+          } else {
+            acc[u][0] = fmaf(ww, __uint_as_float(q.x), acc[u][0]);
+            acc[u][1] = fmaf(ww, __uint_as_float(q.y), acc[u][1]);
+            acc[u][2] = fmaf(ww, __uint_as_float(q.z), acc[u][2]);
+            acc[u][3] = fmaf(ww, __uint_as_float(q.w), acc[u][3]);
+          }
         }
       }
     }

@@ -287,11 +287,14 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
 //              int cand[RT_TM][RT_CMAX] | int flag[RT_TM]
 // RPW = tile rows routed per wave: 2 (a full 16-token tile; compile-time so that the two tokens'
 // dependency chains interleave) or 1 (tpb <= 8 tokens per block).
-template <bool BF16, int NT, int RPW>
+// PRE: the fast scores (bias included) were already written to scores_in[T][E] by
+// gate_tile_kernel; this kernel only selects and runs the exact pass.  scores_in may be the same
+// buffer as scores_out: a token's scores are read before they are written.
+template <bool BF16, int NT, int RPW, bool PRE>
 __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
-    int d, int E, int k, int renorm, int tpb, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_w, float* __restrict__ scores_out) {
+    int d, int E, int k, int renorm, int tpb, const float* scores_in, int32_t* __restrict__ topk_idx,
+    float* __restrict__ topk_w, float* scores_out) {
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);
@@ -312,10 +315,15 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       const int e = lane + MOE_WAVE * q;
       float v = 0.f;
       if (e < E) {
+        if constexpr (PRE) {
+          v = scores_in[static_cast<int64_t>(t0 + row) * E + e];
+          la = fmaxf(la, fabsf(bias ? v - bias[e] : v));
+        } else {
 #pragma unroll
-        for (int w = 0; w < RT_NW; ++w) v += part[(w * RT_TM + row) * E + e];
-        la = fmaxf(la, fabsf(v));
-        if (bias) v += bias[e];
+          for (int w = 0; w < RT_NW; ++w) v += part[(w * RT_TM + row) * E + e];
+          la = fmaxf(la, fabsf(v));
+          if (bias) v += bias[e];
+        }
       }
       s[q] = v;
     }
@@ -323,6 +331,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   };
 
   if (BF16) {
+   if constexpr (!PRE) {
     // ---- fast pass: partial score tiles on the matrix cores ---------------------------------
     const int r = lane & 15;   // token row of the A fragment / expert column of the B fragment
     const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
@@ -383,6 +392,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       }
     }
     __syncthreads();
+   }
     // ---- routing: tile rows are dealt to the waves ----------------------------------------------
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
@@ -913,38 +923,115 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
                         nullptr, nullptr, nullptr, topk_idx, topk_w, scores_out);
 }
 
+// ================================================================================================
+// Small batches with a large gate matrix.  A block of route_kernel pulls the whole w_gate through
+// one CU, and a CU alone gets about 35 GB/s out of a cold L2 (two microseconds of latency on every
+// batch of loads): 30 us for the 1 MB gate of a 128-expert layer, however few tokens there are.
+// With a score buffer from the caller the gate product is spread over the chip instead: a block of
+// gate_tile_kernel computes the fast scores of one 16-token x 16-expert tile (same arithmetic and
+// summation order as route_kernel's fast pass, so the same bits) and writes them to the buffer;
+// route_kernel<.., PRE> then selects from the buffer and runs the exact pass.
+constexpr int RT_PRE_MAX_T = 512;
+
+__global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
+    const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
+    int d, int E, float* __restrict__ scores) {
+  __shared__ float part[RT_NW][RT_TM][16];
+  const int lane = lane_id();
+  const int wave = threadIdx.x / MOE_WAVE;
+  const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * 16;
+  const int row16 = d / 8;
+  const int r = lane & 15;   // token row of the A fragment / expert column of the B fragment
+  const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
+  const uint4* xrow = x + static_cast<int64_t>(min(t0 + r, T - 1)) * row16;
+  const uint4* wrow = wg + static_cast<int64_t>(min(e0 + r, E - 1)) * row16;
+  f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
+  const int c0 = wave * cw;
+  const int c1 = min(row16, c0 + cw);
+  for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
+    uint4 a[RT_BATCH], b[RT_BATCH];
+#pragma unroll
+    for (int u = 0; u < RT_BATCH; ++u) {
+      const int cc = min(cb + 4 * u + kq, row16 - 1);
+      a[u] = xrow[cc];
+      b[u] = wrow[cc];
+    }
+#pragma unroll
+    for (int u = 0; u < RT_BATCH; ++u) {
+      if (cb + 4 * u < c1) {                         // wave-uniform
+        uint4 av = a[u];
+        if (cb + 4 * u + kq >= row16) av = make_uint4(0, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                      __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
+      }
+    }
+  }
+  // D layout: lane holds expert column (lane & 15), token rows 4 * (lane >> 4) + v
+#pragma unroll
+  for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][r] = acc[v];
+  __syncthreads();
+  const int tid = static_cast<int>(threadIdx.x);
+  if (tid < RT_TM * 16) {
+    const int row = tid >> 4, ee = tid & 15;
+    const int64_t t = t0 + row;
+    const int e = e0 + ee;
+    if (t < T && e < E) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < RT_NW; ++w) v += part[w][row][ee];
+      if (bias) v += bias[e];
+      scores[t * E + e] = v;
+    }
+  }
+}
+
 static size_t route_lds_bytes(int E) {
   const size_t dn = E > RT_CMAX ? E : RT_CMAX;
   return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 +
          RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int);
 }
 
-template <bool BF16, int NT, int RPW>
+template <bool BF16, int NT, int RPW, bool PRE>
 static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                            int32_t* idx, float* w, float* scores, int tpb, hipStream_t st) {
+                            int32_t* idx, float* w, const float* scores_in, float* scores, int tpb,
+                            hipStream_t st) {
   static LdsOnce once;
-  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW>),
+  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW, PRE>),
                          static_cast<int>(route_lds_bytes(MOE_MAX_E))) != MOE_OK)
     return MOE_ERR_HIP;
   const int grid = (s->T + tpb - 1) / tpb;
-  hipLaunchKernelGGL((route_kernel<BF16, NT, RPW>), dim3(grid), dim3(RT_THREADS),
+  hipLaunchKernelGGL((route_kernel<BF16, NT, RPW, PRE>), dim3(grid), dim3(RT_THREADS),
                      route_lds_bytes(s->E), st, static_cast<const uint4*>(x),
-                     static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, s->k, s->renorm, tpb, idx,
-                     w, scores);
+                     static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, s->k, s->renorm, tpb,
+                     scores_in, idx, w, scores);
   return launch_status();
 }
 
+// scratch: T x E floats the call may use between its kernels (the caller's score output or its
+// workspace), or null.
 template <bool BF16, int NT>
 static int launch_route(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                        int32_t* idx, float* w, float* scores, hipStream_t st) {
+                        int32_t* idx, float* w, float* scores, float* scratch, hipStream_t st) {
   // Tokens per block: a full 16-row tile when that still gives every CU a few blocks; fewer
   // (the other tile rows idle) for small batches, where latency, not MFMA use, is what counts.
   constexpr int GRID_TARGET = 512;
   int tpb = RT_TM;
   while (tpb > 1 && (s->T + tpb - 1) / tpb < GRID_TARGET) tpb >>= 1;
-  return tpb == RT_TM
-             ? launch_route_rpw<BF16, NT, 2>(s, x, wg, bias, idx, w, scores, tpb, st)
-             : launch_route_rpw<BF16, NT, 1>(s, x, wg, bias, idx, w, scores, tpb, st);
+  if (tpb == RT_TM)
+    return launch_route_rpw<BF16, NT, 2, false>(s, x, wg, bias, idx, w, nullptr, scores, tpb, st);
+  if constexpr (BF16) {
+    // gate product spread over the chip first, if there is somewhere to put the scores and the
+    // gate matrix is large enough (256 KB: 8 us through one CU) to pay for the second launch
+    if (scratch && s->T <= RT_PRE_MAX_T && static_cast<int64_t>(s->E) * s->d * 2 >= 256 * 1024) {
+      hipLaunchKernelGGL(gate_tile_kernel, dim3((s->T + RT_TM - 1) / RT_TM, (s->E + 15) / 16),
+                         dim3(RT_THREADS), 0, st, static_cast<const uint4*>(x),
+                         static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, scratch);
+      if (launch_status() != MOE_OK) return MOE_ERR_HIP;
+      return launch_route_rpw<BF16, NT, 1, true>(s, x, wg, bias, idx, w, scratch, scores, tpb, st);
+    }
+  }
+  return launch_route_rpw<BF16, NT, 1, false>(s, x, wg, bias, idx, w, nullptr, scores, tpb, st);
 }
 
 template <int NT, int TILES>
@@ -990,17 +1077,17 @@ static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, 
 
 template <int NT>
 static int launch_route_bf16(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                             int32_t* idx, float* w, float* scores, hipStream_t st) {
+                             int32_t* idx, float* w, float* scores, float* scratch, hipStream_t st) {
   int rc = MOE_OK;
   if (try_route_tile<NT>(s, x, wg, bias, idx, w, scores, st, &rc)) return rc;
-  return launch_route<true, NT>(s, x, wg, bias, idx, w, scores, st);
+  return launch_route<true, NT>(s, x, wg, bias, idx, w, scores, scratch, st);
 }
 
 }  // namespace moe
 
-extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
-                         const float* gate_bias, int32_t* topk_idx, float* topk_w,
-                         float* scores_out, void* hip_stream) {
+static int route_impl(const moe_shape_t* shape, const void* x, const void* w_gate,
+                      const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = moe::check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
@@ -1008,14 +1095,34 @@ extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_
   if (!moe::aligned16(x) || !moe::aligned16(w_gate)) return MOE_ERR_INVALID_ARG;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int E = shape->E;
+  // somewhere to keep T x E fast scores between two kernels: the caller's score output, else its
+  // workspace if that is large enough
+  float* scratch = scores_out;
+  if (!scratch && workspace && moe::aligned16(workspace) &&
+      workspace_bytes >= static_cast<size_t>(shape->T) * E * sizeof(float))
+    scratch = static_cast<float*>(workspace);
   if (shape->dtype == MOE_BF16) {
-    if (E <= 16) return moe::launch_route_bf16<1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 32) return moe::launch_route_bf16<2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 64) return moe::launch_route_bf16<4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    if (E <= 128) return moe::launch_route_bf16<8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-    return moe::launch_route_bf16<16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+    if (E <= 16) return moe::launch_route_bf16<1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
+    if (E <= 32) return moe::launch_route_bf16<2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
+    if (E <= 64) return moe::launch_route_bf16<4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
+    if (E <= 128) return moe::launch_route_bf16<8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
+    return moe::launch_route_bf16<16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
   }
-  if (E <= 64) return moe::launch_route<false, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-  if (E <= 128) return moe::launch_route<false, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
-  return moe::launch_route<false, 16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, st);
+  if (E <= 64) return moe::launch_route<false, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
+  if (E <= 128) return moe::launch_route<false, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
+  return moe::launch_route<false, 16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
+}
+
+extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
+                         const float* gate_bias, int32_t* topk_idx, float* topk_w,
+                         float* scores_out, void* hip_stream) {
+  return route_impl(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, 0, hip_stream);
+}
+
+extern "C" int moe_route_ws(const moe_shape_t* shape, const void* x, const void* w_gate,
+                            const float* gate_bias, int32_t* topk_idx, float* topk_w,
+                            float* scores_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+  return route_impl(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, workspace,
+                    workspace_bytes, hip_stream);
 }

@@ -55,8 +55,8 @@ class MoeBuffers:
         gather_in_ffn: the up-projection reads x through the permutation map and x_perm is not
         materialised (same results, bit for bit)."""
         s = torch.cuda.current_stream() if stream is None else stream
-        B.moe_route(self.shape, x, w_gate, gate_bias, self.topk_idx, self.topk_w,
-                    self.scores if export_scores else None, s)
+        B.moe_route_ws(self.shape, x, w_gate, gate_bias, self.topk_idx, self.topk_w,
+                       self.scores if export_scores else None, self.workspace, self.ws_bytes, s)
         B.moe_count_and_permute(self.shape, x, self.topk_idx, self.counts, self.offsets,
                                 self.dst_row, self.src_assign, None if gather_in_ffn else self.x_perm,
                                 self.workspace, self.ws_bytes, s)
@@ -115,7 +115,8 @@ class LoadPredictor:
 
     def enqueue(self, x, w_pred, gate_bias=None, cv_threshold=0.2, stream=None):
         s = torch.cuda.current_stream() if stream is None else stream
-        B.moe_route(self.shape, x, w_pred, gate_bias, self.topk_idx, self.topk_w, None, s)
+        B.moe_route_ws(self.shape, x, w_pred, gate_bias, self.topk_idx, self.topk_w, None,
+                       self.workspace, self.ws_bytes, s)
         B.moe_count_and_permute(self.shape, None, self.topk_idx, self.counts, self.offsets,
                                 self.dst_row, self.src_assign, None, self.workspace, self.ws_bytes, s)
         # memory in units of one expert: the cap is the number of additional replicas

@@ -68,6 +68,7 @@ def test_shape_validation_happens_before_any_launch(lib):
         assert ei.value.code == -2
     # null pointers are rejected by every call, on the host
     for call in (lambda: B.moe_route(ok, None, None, None, None, None),
+                 lambda: B.moe_route_ws(ok, None, None, None, None, None, None, None, 0),
                  lambda: B.moe_count_and_permute(ok, None, None, None, None, None, None, None,
                                                  None, 0),
                  lambda: B.moe_grouped_ffn(ok, None, None, None, None, None, None, None),
@@ -82,15 +83,20 @@ def test_shape_validation_happens_before_any_launch(lib):
     # T = 0 is a no-op for the calls that only touch per-token data
     empty = B.make_shape(0, 128, 8, 2, 256, B.MOE_BF16, 1)
     B.moe_route(empty, None, None, None, None, None)
+    B.moe_route_ws(empty, None, None, None, None, None, None, None, 0)
     B.moe_grouped_ffn(empty, None, None, None, None, None, None, None)
     B.moe_combine(empty, None, None, None, None)
 
 
 def test_workspace_size_grows_with_tokens(lib):
-    small = B.moe_workspace_bytes(B.make_shape(256, 128, 64, 6, 256, B.MOE_BF16, 0))
+    small = B.moe_workspace_bytes(B.make_shape(1024, 128, 64, 6, 256, B.MOE_BF16, 0))
     large = B.moe_workspace_bytes(B.make_shape(8192, 128, 64, 6, 256, B.MOE_BF16, 0))
-    assert large >= 32 * 64 * 4 and small >= 64 * 4 and large > small
+    assert large >= 32 * 64 * 4 and small >= 4 * 64 * 4 and large > small
     assert small % 256 == 0 and large % 256 == 0
+    # batches of at most 512 tokens: room for T x E fp32 scores between moe_route_ws's two kernels
+    decode = B.moe_workspace_bytes(B.make_shape(32, 4096, 128, 8, 1536, B.MOE_BF16, 1))
+    assert decode >= 32 * 128 * 4
+    assert B.moe_workspace_bytes(B.make_shape(512, 128, 256, 8, 256, B.MOE_BF16, 1)) >= 512 * 256 * 4
 
 
 def test_product_package_does_not_import_the_oracle(repo_root):

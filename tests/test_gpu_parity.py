@@ -201,6 +201,65 @@ def test_route_large_batch_without_scores_output():
     assert np.all(np.abs(host(w) - rw) <= 1e-5 * np.abs(rw) + 1e-9)
 
 
+# Small batches with a gate matrix of at least 256 KB: with a workspace (or a score output) the
+# gate product runs as a kernel of its own over the whole chip and the selection reads its scores.
+SMALL_ROUTE_WS_CASES = [
+    dict(T=32, d=4096, E=128, k=8, renorm=1),      # the decode-shaped layer's routing
+    dict(T=77, d=1024, E=128, k=8, renorm=0),      # exactly 256 KB
+    dict(T=130, d=2056, E=200, k=5, renorm=1),     # ragged hidden size, E > 128, E % 16 != 0
+    dict(T=512, d=2048, E=64, k=6, renorm=1),      # the largest batch that takes this path
+    dict(T=1, d=4096, E=33, k=33, renorm=1),       # one token, k = E
+]
+
+
+def gpu_route_ws(cfg, x, w_gate, bias, with_ws, with_scores):
+    T, E, k = cfg.T, cfg.E, cfg.k
+    sh = shape_of(cfg)
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((T, k), dtype=torch.float32, device="cuda")
+    sc = torch.full((T, E), -3.0, dtype=torch.float32, device="cuda") if with_scores else None
+    nb = B.moe_workspace_bytes(sh)
+    assert nb >= T * E * 4
+    ws = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda") if with_ws else None
+    B.moe_route_ws(sh, dev(x), dev(w_gate), dev(bias), idx, w, sc, ws, nb if with_ws else 0)
+    torch.cuda.synchronize()
+    return host(idx), host(w), (host(sc) if with_scores else None)
+
+
+@pytest.mark.parametrize("case", SMALL_ROUTE_WS_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}".format(**c))
+def test_route_with_workspace_matches_oracle_and_plain_route(case):
+    cfg = si.small_config(F=64, **case)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    x, wg = L["x"].copy(), L["w_gate"].copy()
+    wg[cfg.E - 1] = wg[0]                           # an exact tie between the first and the last expert
+    x[cfg.T // 2] = 0                               # and a token whose scores are all equal
+    bias = np.linspace(-1.0, 1.0, cfg.E).astype(np.float32)
+    for b in (None, bias):
+        ridx, rw, rsc = orc.route(x, wg, cfg.k, cfg.renorm, b)
+        pidx, pw, psc = gpu_route(cfg, x, wg, b)    # moe_route: one kernel
+        assert np.array_equal(pidx, ridx)
+        for with_ws, with_scores in ((True, False), (False, True), (True, True)):
+            idx, w, sc = gpu_route_ws(cfg, x, wg, b, with_ws, with_scores)
+            assert np.array_equal(idx, ridx), (with_ws, with_scores)
+            assert np.all(np.abs(w - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+            assert np.array_equal(w, pw)            # same scores, same arithmetic: same bits
+            if with_scores:
+                assert np.array_equal(sc, psc)
+
+
+def test_route_ws_without_usable_workspace_is_plain_route():
+    cfg = si.small_config(T=32, d=4096, E=128, k=8, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    ridx, rw, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm, None)
+    idx = torch.full((cfg.T, cfg.k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    small = torch.zeros((256,), dtype=torch.uint8, device="cuda")       # too small: ignored
+    B.moe_route_ws(shape_of(cfg), dev(L["x"]), dev(L["w_gate"]), None, idx, w, None, small, 256)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(idx), ridx)
+    assert np.all(np.abs(host(w) - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+
+
 # ----------------------------------------------------------------------------- count + permute
 def gpu_dispatch(cfg, x, idx):
     T, E, k, d = cfg.T, cfg.E, cfg.k, cfg.d
