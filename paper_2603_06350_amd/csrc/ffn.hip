@@ -677,6 +677,13 @@ static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, 
   int rc = MOE_OK;
   // Overlap pays when the main launches are long; decode-shaped calls stay on one stream.
   const bool overlap = A / g1.E >= 128;
+  if (A / g1.E < 16) {
+    // a handful of rows per expert (decode-shaped calls): everything as 64-row tiles in one launch
+    // per GEMM; a main launch would find no tile and only cost its start-up
+    if (up && (rc = launch_mfma<64, true, 2, 4, 4>(g1, TILES_ALL, 64, A, st)) != MOE_OK) return rc;
+    if (down) rc = launch_mfma<64, false, 2, 4, 4>(g2, TILES_ALL, 64, A, st);
+    return rc;
+  }
   if (!overlap) {
     if (up) {
       if ((rc = mfma_gemm_main<true>(g1, A, st)) != MOE_OK) return rc;

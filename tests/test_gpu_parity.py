@@ -379,6 +379,18 @@ FFN_CASES = [
 ]
 
 
+def test_grouped_ffn_few_rows_per_expert_with_one_hot_expert():
+    # fewer than 16 rows per expert on average (everything runs as 64-row tiles in one launch per
+    # GEMM), but one expert holds several tiles' worth of rows and most are empty
+    cfg = si.small_config(T=400, d=256, E=64, k=1, F=384)
+    L = si.make_layer(cfg)
+    rng = np.random.default_rng(5)
+    idx = np.where(rng.random((cfg.T, 1)) < 0.8, 5, rng.integers(0, 64, size=(cfg.T, 1))).astype(np.int32)
+    counts, _ = orc.expert_load(idx, cfg.E)
+    assert counts[5] > 4 * 64 and (counts == 0).sum() > 10
+    check_ffn(cfg, L, idx)
+
+
 @pytest.mark.parametrize("case", FFN_CASES, ids=lambda c: "T{T}_d{d}_E{E}_k{k}_F{F}".format(**c))
 def test_grouped_ffn_matches_oracle(case):
     cfg = si.small_config(**case)
