@@ -2,7 +2,12 @@
 // network routes each token to its experts; the gate is a bias-free d x E linear
 // map, Sections 5 and 6.6).
 //
-// One block = one 16-row MFMA tile of tokens, 8 waves.  Large batches fill all 16
+// Three forms, chosen on the host by the shape: route_kernel (below; every batch size, every
+// dtype), route_tile_kernel (large bf16 batches: several token tiles per block share one pass of
+// w_gate through LDS, selection by per-lane tournaments) and gate_tile_kernel + route_kernel<PRE>
+// (small batches with a workspace: the gate product spread over the chip first).
+//
+// route_kernel: one block = one 16-row MFMA tile of tokens, 8 waves.  Large batches fill all 16
 // rows; small ones give a block fewer tokens (down to one, the other rows idle) so
 // that the batch still spreads over the chip.  The waves split the hidden dimension;
 // each runs v_mfma_f32_16x16x32_bf16 on its slice straight from global memory (x is
@@ -757,7 +762,7 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   const int ks = wave / TILES, tile = wave % TILES;        // waves 0..TILES-1 (ks = 0) own the tiles
   const int t0 = blockIdx.x * (16 * TILES);
   const int row16 = d / 8;
-  const int tok = lane & 15, g = lane >> 4;
+  const int tok = lane & 15;
   const int kgrp = ((lane >> 4) & 1) * 2 + (lane >> 5);     // which 16-byte chunk of a k-step's four
   const int cs = row16 / KS;                                // chunks per slice, a multiple of 8
   const int KT = cs / 8;                                    // 64-element stages per slice
