@@ -63,6 +63,10 @@ struct GemmArgs {
   const int32_t* src_assign;
   int k_div;
   int a_rows;       // rows of `a` (gathered row numbers are clamped to it)
+  int n_cu;         // compute units of the device (the main/small split is priced in rounds of it)
+  // n-tiles and K stages of the up- and the down-projection of the call this GEMM belongs to:
+  // both take the main/small decision on the same sum, so they take the same one
+  int pair_n_tiles[2], pair_kt[2];
 };
 
 // Row of `a` that holds GEMM row r.
@@ -82,6 +86,13 @@ struct TileCoord {
 // TILES_ALL lists the full tiles and the remainder, TILES_MAIN drops remainders of at
 // most SMALL_ROWS rows, TILES_SMALL lists only those.  Tile order: expert-major, then
 // n-tile, then m-tile (m fastest), cut into 8 contiguous ranges, one per XCD.
+//
+// TILES_MAIN and TILES_SMALL belong to two launches over the same offsets, and both (in both
+// GEMMs of a call) take the same decision from them: if carrying the small remainders as (mostly
+// empty) main tiles costs no more rounds of the chip, weighted by the K length of each GEMM,
+// than the main tiles alone plus the small tiles at 0.6 of a main tile each (a figure that
+// reproduces which form measured faster on six layer shapes), the main launches take every
+// remainder and the small launches find nothing to do.
 __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int32_t* __restrict__ offsets = p.offsets;
   const int E = p.E, n_tiles = p.n_tiles, bm = p.bm_main, mode = p.mode;
@@ -89,22 +100,52 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int per = (E + MOE_WAVE - 1) / MOE_WAVE;  // <= 4
   const int e0 = lane * per;
   int mt[4], ob[4], oe[4];                       // tiles, first and end row of this lane's experts
-  int local = 0;
+  int t_all[4], t_small[4];
+  int n_all = 0, n_small = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int e = e0 + i;
-    int t = 0;
     ob[i] = 0;
     oe[i] = 0;
+    t_all[i] = 0;
+    t_small[i] = 0;
     if (i < per && e < E) {
       ob[i] = offsets[e];
       oe[i] = offsets[e + 1];
       const int c = max(oe[i] - ob[i], 0);
       const int full = c / bm, rem = c % bm;
-      if (mode == TILES_ALL) t = full + (rem > 0 ? 1 : 0);
-      else if (mode == TILES_MAIN) t = full + (rem > SMALL_ROWS ? 1 : 0);
-      else t = (rem > 0 && rem <= SMALL_ROWS) ? 1 : 0;
+      t_all[i] = full + (rem > 0 ? 1 : 0);
+      t_small[i] = (rem > 0 && rem <= SMALL_ROWS) ? 1 : 0;
     }
+    n_all += t_all[i];
+    n_small += t_small[i];
+  }
+  bool fold = false;                             // small remainders ride in the main launch
+  if (mode != TILES_ALL) {
+#pragma unroll
+    for (int off = 1; off < MOE_WAVE; off <<= 1) {
+      n_all += __shfl_xor(n_all, off);
+      n_small += __shfl_xor(n_small, off);
+    }
+    const int64_t cu = p.n_cu > 0 ? p.n_cu : 256;
+    int64_t cost_fold = 0, cost_split = 0;       // in tenths of a tile-stage on every CU
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int64_t tiles_all = static_cast<int64_t>(n_all) * p.pair_n_tiles[g];
+      const int64_t tiles_small = static_cast<int64_t>(n_small) * p.pair_n_tiles[g];
+      const int64_t rounds_all = (tiles_all + cu - 1) / cu;
+      const int64_t rounds_main = (tiles_all - tiles_small + cu - 1) / cu;
+      cost_fold += p.pair_kt[g] * rounds_all * cu * 10;
+      cost_split += p.pair_kt[g] * (rounds_main * cu * 10 + tiles_small * 6);
+    }
+    fold = cost_fold <= cost_split;
+  }
+  int local = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int t = t_all[i];
+    if (mode == TILES_MAIN) t = fold ? t_all[i] : t_all[i] - t_small[i];
+    else if (mode == TILES_SMALL) t = fold ? 0 : t_small[i];
     mt[i] = t;
     local += t;
   }
@@ -582,18 +623,26 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
   }
 }
 
+// Compute units of the current device, looked up once per device (0 if the query fails: the
+// kernels then assume 256).
+static int device_cu_count() {
+  static int cached[MOE_MAX_DEVICES] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MOE_MAX_DEVICES) return 0;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
+
 // Upper bounds on the number of m-tiles that need no knowledge of the counts: an expert has at
-// most floor(c/bm) full tiles (sum <= A/bm) and one remainder; a main-list remainder has more
-// than SMALL_ROWS rows, so there are at most A/(SMALL_ROWS+1) main tiles in total.
+// most floor(c/bm) full tiles (sum <= A/bm) and one remainder.
 static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
   const int64_t e_cap = E < A ? E : A;
   if (mode == TILES_SMALL) return e_cap;
-  const int64_t ub = A / bm + e_cap;
-  if (mode == TILES_MAIN) {
-    const int64_t by_rows = A / (SMALL_ROWS + 1);
-    return ub < by_rows ? ub : by_rows;
-  }
-  return ub;
+  return A / bm + e_cap;   // TILES_MAIN may take every remainder: the same bound as TILES_ALL
 }
 
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
@@ -649,7 +698,9 @@ static int mfma_gemm_small(const GemmArgs& g, int64_t A, hipStream_t st) {
 // side stream per device (default priority, created on first use, kept for the life of the
 // process) is forked from the caller's stream with an event and joined back with another, so
 // the caller sees ordinary stream semantics; the rows the two chains touch are disjoint (a
-// remainder's h rows are written and read by the side chain only).
+// remainder's h rows are written and read by the side chain only, or, when the small remainders
+// ride in the main launches, by the main chain only: both GEMMs of a call take that decision
+// together).
 struct SideStream {
   hipStream_t stream = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
@@ -729,14 +780,21 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int64_t A = static_cast<int64_t>(shape->T) * shape->k;
   const int d = shape->d, F = shape->F, E = shape->E;
+  const int n_cu = device_cu_count();
   GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_ALL, 64,
-              src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A)};
+              src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A), n_cu, {0, 0}, {0, 0}};
   GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_ALL, 64,
-              nullptr, 1, static_cast<int>(A)};
+              nullptr, 1, static_cast<int>(A), n_cu, {0, 0}, {0, 0}};
   const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
     g2.n_tiles = (d + 255) / 256;
+    for (GemmArgs* g : {&g1, &g2}) {
+      g->pair_n_tiles[0] = g1.n_tiles;
+      g->pair_n_tiles[1] = g2.n_tiles;
+      g->pair_kt[0] = d / 64;
+      g->pair_kt[1] = F / 64;
+    }
     return mfma_ffn(g1, g2, up, down, A, st);
   }
   g1.n_tiles = (F + 63) / 64;
