@@ -93,6 +93,21 @@ struct TileCoord {
 // than the main tiles alone plus the small tiles at 0.6 of a main tile each (a figure that
 // reproduces which form measured faster on six layer shapes), the main launches take every
 // remainder and the small launches find nothing to do.
+// Inclusive prefix sum over the wave by DPP: four shifted adds inside each row of 16 lanes, then
+// the totals of rows 0 and 2 go to rows 1 and 3, and the total of rows 0-1 to rows 2 and 3.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ int dpp_add(int x) {
+  return x + __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xF, true);
+}
+__device__ __forceinline__ int wave_scan_add(int x) {
+  x = dpp_add<0x111, 0xF>(x);   // row_shr:1
+  x = dpp_add<0x112, 0xF>(x);   // row_shr:2
+  x = dpp_add<0x114, 0xF>(x);   // row_shr:4
+  x = dpp_add<0x118, 0xF>(x);   // row_shr:8
+  x = dpp_add<0x142, 0xA>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_add<0x143, 0xC>(x);   // row_bcast:31 into rows 2 and 3
+  return x;
+}
+
 __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int32_t* __restrict__ offsets = p.offsets;
   const int E = p.E, n_tiles = p.n_tiles, bm = p.bm_main, mode = p.mode;
@@ -120,23 +135,26 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
     n_all += t_all[i];
     n_small += t_small[i];
   }
+  // prefix sums over the experts (lane order = expert order) of both counts at once; the mode's own
+  // list is a combination of the two
+  const int incl_all = wave_scan_add(n_all), incl_small = wave_scan_add(n_small);
   bool fold = false;                             // small remainders ride in the main launch
   if (mode != TILES_ALL) {
-#pragma unroll
-    for (int off = 1; off < MOE_WAVE; off <<= 1) {
-      n_all += __shfl_xor(n_all, off);
-      n_small += __shfl_xor(n_small, off);
-    }
-    const int64_t cu = p.n_cu > 0 ? p.n_cu : 256;
+    n_all = __builtin_amdgcn_readlane(incl_all, MOE_WAVE - 1);
+    n_small = __builtin_amdgcn_readlane(incl_small, MOE_WAVE - 1);
+    // (tile counts fit 32 bits: the host refuses grids beyond 2^31 - 1 blocks, and a grid is an
+    // upper bound of its tile count)
+    const uint32_t cu = p.n_cu > 0 ? p.n_cu : 256;
     int64_t cost_fold = 0, cost_split = 0;       // in tenths of a tile-stage on every CU
 #pragma unroll
     for (int g = 0; g < 2; ++g) {
-      const int64_t tiles_all = static_cast<int64_t>(n_all) * p.pair_n_tiles[g];
-      const int64_t tiles_small = static_cast<int64_t>(n_small) * p.pair_n_tiles[g];
-      const int64_t rounds_all = (tiles_all + cu - 1) / cu;
-      const int64_t rounds_main = (tiles_all - tiles_small + cu - 1) / cu;
-      cost_fold += p.pair_kt[g] * rounds_all * cu * 10;
-      cost_split += p.pair_kt[g] * (rounds_main * cu * 10 + tiles_small * 6);
+      const uint32_t tiles_all = static_cast<uint32_t>(n_all) * p.pair_n_tiles[g];
+      const uint32_t tiles_small = static_cast<uint32_t>(n_small) * p.pair_n_tiles[g];
+      const uint32_t rounds_all = (tiles_all + cu - 1) / cu;
+      const uint32_t rounds_main = (tiles_all - tiles_small + cu - 1) / cu;
+      cost_fold += static_cast<int64_t>(p.pair_kt[g]) * rounds_all * cu * 10;
+      cost_split += static_cast<int64_t>(p.pair_kt[g]) *
+                    (static_cast<int64_t>(rounds_main) * cu * 10 + static_cast<int64_t>(tiles_small) * 6);
     }
     fold = cost_fold <= cost_split;
   }
@@ -149,14 +167,10 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
     mt[i] = t;
     local += t;
   }
-  int incl = local;
-#pragma unroll
-  for (int off = 1; off < MOE_WAVE; off <<= 1) {
-    const int up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
-  }
-  // readfirstlane: the results are wave-uniform; tell the compiler so they live in SGPRs
-  const int total = __builtin_amdgcn_readfirstlane(__shfl(incl, MOE_WAVE - 1)) * n_tiles;
+  int incl = incl_all;
+  if (mode == TILES_MAIN) incl = fold ? incl_all : incl_all - incl_small;
+  else if (mode == TILES_SMALL) incl = fold ? 0 : incl_small;
+  const int total = __builtin_amdgcn_readlane(incl, MOE_WAVE - 1) * n_tiles;
   const int per_xcd = (total + 7) / 8;
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
@@ -178,14 +192,14 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   }
   const unsigned long long who = __ballot(found_e >= 0);
   if (who == 0ull) return false;  // inconsistent offsets: no tile
-  const int src = __ffsll(static_cast<long long>(who)) - 1;
-  const int e = __builtin_amdgcn_readfirstlane(__shfl(found_e, src));
-  const int loc = __builtin_amdgcn_readfirstlane(__shfl(found_local, src));
-  const int m_tiles = __builtin_amdgcn_readfirstlane(__shfl(found_mt, src));
+  const int src = __ffsll(static_cast<long long>(who)) - 1;   // wave-uniform: reads of that lane
+  const int e = __builtin_amdgcn_readlane(found_e, src);
+  const int loc = __builtin_amdgcn_readlane(found_local, src);
+  const int m_tiles = __builtin_amdgcn_readlane(found_mt, src);
   const int m_idx = loc % m_tiles;
   // the lane that owns the expert already holds its row range: no second trip to memory
-  const int seg_begin = max(__builtin_amdgcn_readfirstlane(__shfl(found_ob, src)), 0);
-  const int seg_end = min(__builtin_amdgcn_readfirstlane(__shfl(found_oe, src)), p.rows);
+  const int seg_begin = max(__builtin_amdgcn_readlane(found_ob, src), 0);
+  const int seg_end = min(__builtin_amdgcn_readlane(found_oe, src), p.rows);
   tc.e = e;
   tc.n_tile = loc / m_tiles;
   if (mode == TILES_SMALL) {
