@@ -85,8 +85,9 @@ int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
  * the whole chip by a kernel of its own and the selection reads its scores from the
  * workspace; without a workspace (and without scores_out) every block has to pull
  * the whole gate matrix through one compute unit.  workspace: 16-byte aligned,
- * contents ignored on entry and undefined on return; if it is NULL or smaller than
- * moe_workspace_bytes() the call behaves like moe_route (no error).
+ * contents ignored on entry and undefined on return; moe_workspace_bytes() is
+ * always enough.  If it is NULL, misaligned or smaller than T*E*4 bytes the call
+ * behaves like moe_route (no error).
  */
 int moe_route_ws(const moe_shape_t* shape, const void* x, const void* w_gate,
                  const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
