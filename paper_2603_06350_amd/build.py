@@ -39,7 +39,7 @@ def build(verbose: bool = False, extra=(), out: str = LIB) -> str:
     return out
 
 
-MICROBENCH = ["mfma_rate", "l2_to_lds_stream"]
+MICROBENCH = ["mfma_rate", "l2_to_lds_stream", "hbm_read_stream"]
 
 
 def build_microbench(verbose: bool = False) -> list:
