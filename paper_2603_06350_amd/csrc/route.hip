@@ -175,18 +175,15 @@ __device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, 
   return 0;
 }
 
-// Exact gate sums (fp64) of one token for up to RT_CMAX listed experts, this wave's part of the
-// hidden dimension.  Lane = (candidate slot, one of four sub-slices).
+// Exact gate sum (fp64) of one (token row, expert row) pair per candidate slot, this wave's part
+// of the hidden dimension.  Lane = (candidate slot lane % RT_CMAX, one of four sub-slices); the
+// four sub-slice sums of a slot are added by two lane exchanges; the lanes of sub-slice 0 return
+// the slot's sum.
 template <bool BF16>
-__device__ void exact_candidates(const uint4* __restrict__ xrow, const uint4* __restrict__ wg,
-                                 int row16, const int* __restrict__ cand, int n, int wave,
-                                 double* __restrict__ dpart) {
-  const int lane = lane_id();
-  const int c = lane & (RT_CMAX - 1);
-  const int sub = lane / RT_CMAX;
+__device__ __forceinline__ double exact_slot_sum(const uint4* __restrict__ xrow,
+                                                 const uint4* __restrict__ wrow, int row16, int wave) {
+  const int sub = lane_id() / RT_CMAX;
   constexpr int NSUB = MOE_WAVE / RT_CMAX;
-  const int e = cand[c < n ? c : 0];
-  const uint4* wrow = wg + static_cast<int64_t>(e) * row16;
   const int cw = (row16 + RT_NW - 1) / RT_NW;
   const int c0 = wave * cw;
   const int c1 = min(row16, c0 + cw);
@@ -225,7 +222,19 @@ __device__ void exact_candidates(const uint4* __restrict__ xrow, const uint4* __
   }
   acc += __shfl_xor(acc, 16);
   acc += __shfl_xor(acc, 32);
-  if (sub == 0 && c < n) dpart[wave * RT_CMAX + c] = acc;
+  return acc;
+}
+
+// Exact gate sums of one token for up to RT_CMAX listed experts: dpart[wave * RT_CMAX + slot].
+template <bool BF16>
+__device__ void exact_candidates(const uint4* __restrict__ xrow, const uint4* __restrict__ wg,
+                                 int row16, const int* __restrict__ cand, int n, int wave,
+                                 double* __restrict__ dpart) {
+  const int lane = lane_id();
+  const int c = lane & (RT_CMAX - 1);
+  const int e = cand[c < n ? c : 0];
+  const double acc = exact_slot_sum<BF16>(xrow, wg + static_cast<int64_t>(e) * row16, row16, wave);
+  if (lane < RT_CMAX && c < n) dpart[wave * RT_CMAX + c] = acc;
 }
 
 // Exact partial gate sums of one token over this wave's part of the hidden
@@ -670,54 +679,20 @@ __device__ void select_tile(const float (&s)[S], float lmax, bool check, bool co
   }
 }
 
-// Exact gate sums (fp64) of up to RT_CMAX (token, candidate expert) pairs, this wave's part of the
-// hidden dimension: the arithmetic of exact_candidates with a token of its own per candidate
-// slot.  pairs[] holds (row | position in the token's candidate list << 16).
+// Exact gate sums of up to RT_CMAX (token, candidate expert) pairs, a token of its own per slot.
+// pairs[] holds (row | position in the token's candidate list << 16).
 // Result: dpart[wave * RT_CMAX + pair].
 __device__ void exact_pairs(const uint4* __restrict__ x, const uint4* __restrict__ wg, int row16,
                             int64_t t0, const int* __restrict__ pairs, int npairs,
                             const int* __restrict__ cand_all, int wave, double* __restrict__ dpart) {
   const int lane = lane_id();
   const int c = lane & (RT_CMAX - 1);
-  const int sub = lane / RT_CMAX;
-  constexpr int NSUB = MOE_WAVE / RT_CMAX;
   const int entry = pairs[c < npairs ? c : 0];
   const int prow = entry & 0xFFFF, pos = entry >> 16;
   const int e = cand_all[prow * RT_CMAX + pos];
-  const uint4* xrow = x + (t0 + prow) * row16;
-  const uint4* wrow = wg + static_cast<int64_t>(e) * row16;
-  const int cw = (row16 + RT_NW - 1) / RT_NW;
-  const int c0 = wave * cw;
-  const int c1 = min(row16, c0 + cw);
-  double acc = 0.0;
-  constexpr int XB = 8;
-  for (int cb = c0 + sub; cb < c1; cb += XB * NSUB) {
-    uint4 av[XB], bv[XB];
-#pragma unroll
-    for (int u = 0; u < XB; ++u) {
-      const int cc = min(cb + u * NSUB, row16 - 1);
-      av[u] = xrow[cc];
-      bv[u] = wrow[cc];
-    }
-#pragma unroll
-    for (int u = 0; u < XB; ++u) {
-      if (cb + u * NSUB < c1) {
-        const uint4 a = av[u];
-        const uint4 b = bv[u];
-        acc = fma(static_cast<double>(bf16lo(a.x)), static_cast<double>(bf16lo(b.x)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.x)), static_cast<double>(bf16hi(b.x)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.y)), static_cast<double>(bf16lo(b.y)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.y)), static_cast<double>(bf16hi(b.y)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.z)), static_cast<double>(bf16lo(b.z)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.z)), static_cast<double>(bf16hi(b.z)), acc);
-        acc = fma(static_cast<double>(bf16lo(a.w)), static_cast<double>(bf16lo(b.w)), acc);
-        acc = fma(static_cast<double>(bf16hi(a.w)), static_cast<double>(bf16hi(b.w)), acc);
-      }
-    }
-  }
-  acc += __shfl_xor(acc, 16);
-  acc += __shfl_xor(acc, 32);
-  if (sub == 0 && c < npairs) dpart[wave * RT_CMAX + c] = acc;
+  const double acc = exact_slot_sum<true>(x + (t0 + prow) * row16, wg + static_cast<int64_t>(e) * row16,
+                                          row16, wave);
+  if (lane < RT_CMAX && c < npairs) dpart[wave * RT_CMAX + c] = acc;
 }
 
 template <int NT, int TILES>
