@@ -27,6 +27,7 @@
 // up to fp64 rounding, and the token is routed again.  fp32 inputs always take the
 // exact path for all experts.
 #include <type_traits>
+#include <utility>
 
 #include "moe_internal.h"
 
@@ -488,17 +489,27 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
 // same protocol as above (exact re-scoring of the listed candidates by the whole block, four
 // tokens per pass), after which their lanes patch the scores they hold and select once more.
 constexpr int RT_KSEL = 16;      // largest k this path handles (the picks of a tile sit in LDS)
-constexpr int RT_NSTAGE = 3;     // LDS ring of w_gate stages
 
 __device__ __forceinline__ int rt_swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <class F, int... I>
+__device__ __forceinline__ void rt_unrolled_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void rt_unrolled(F&& f) {
+  rt_unrolled_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int N> __device__ __forceinline__ void rt_wait_vmcnt() {
-  static_assert(N >= 0 && N <= 8, "vmcnt immediate");
+  static_assert(N >= 0 && N <= 16, "vmcnt immediate");
 #define MOE_RT_VMCNT_CASE(n) \
   if constexpr (N == n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory");
   MOE_RT_VMCNT_CASE(0) MOE_RT_VMCNT_CASE(1) MOE_RT_VMCNT_CASE(2) MOE_RT_VMCNT_CASE(3)
   MOE_RT_VMCNT_CASE(4) MOE_RT_VMCNT_CASE(5) MOE_RT_VMCNT_CASE(6) MOE_RT_VMCNT_CASE(7)
-  MOE_RT_VMCNT_CASE(8)
+  MOE_RT_VMCNT_CASE(8) MOE_RT_VMCNT_CASE(9) MOE_RT_VMCNT_CASE(10) MOE_RT_VMCNT_CASE(11)
+  MOE_RT_VMCNT_CASE(12) MOE_RT_VMCNT_CASE(13) MOE_RT_VMCNT_CASE(14) MOE_RT_VMCNT_CASE(15)
+  MOE_RT_VMCNT_CASE(16)
 #undef MOE_RT_VMCNT_CASE
 }
 
@@ -700,8 +711,11 @@ struct RouteTileLds {
   static constexpr int KS = RT_NW / TILES;
   static constexpr int ROWS = KS * NT * 16;                 // w_gate rows (expert, slice) per stage
   static constexpr int STAGE = ROWS * 128;
+  // stages in the LDS ring (one is being read, the others are in flight): small stages move few
+  // bytes each, so they need a deeper ring to keep the same number of bytes on their way from HBM
+  static constexpr int NS = STAGE <= 4096 ? 6 : (STAGE <= 8192 ? 4 : 3);
   static constexpr int PART = RT_NW * NT * 4 * MOE_WAVE * 4;                // aliases the stages
-  static constexpr int RING = RT_NSTAGE * STAGE > PART ? RT_NSTAGE * STAGE : PART;
+  static constexpr int RING = NS * STAGE > PART ? NS * STAGE : PART;
   static constexpr int PICKS = RING;                        // float/int [RT_NW][2][RT_KSEL + 1][16]
   static constexpr int CAND = PICKS + RT_NW * 2 * (RT_KSEL + 1) * 16 * 4;   // int [16 TILES][RT_CMAX]
   static constexpr int CCOUNT = CAND + TILES * 16 * RT_CMAX * 4;            // int [16 TILES]
@@ -762,7 +776,8 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   // ---- x -> registers: lane (tok, kgrp) of k-step j of stage kt holds chunk 8 kt + 4 j + kgrp
   const int t_ld = min(t0 + tile * 16 + tok, T - 1);
   const uint4* xrow = x + static_cast<int64_t>(t_ld) * row16 + ks * cs + kgrp;
-  uint4 a[RT_NSTAGE][2];
+  constexpr int NS = L::NS, DIST = NS - 1;
+  uint4 a[NS][2];
   auto issue = [&](int kt, auto slot_c) {
     constexpr int SLOT = decltype(slot_c)::value;
 #pragma unroll
@@ -785,14 +800,21 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   using std::integral_constant;
-  issue(0, integral_constant<int, 0>{});
-  if (KT > 1) issue(1, integral_constant<int, 1>{});
+  // prologue: the first DIST stages; then stage kt waits for its own loads (up to DIST - 1 later
+  // stages may still be in flight), and, after the barrier that also frees the slot of stage
+  // kt - 1, sends the loads of stage kt + DIST into that slot
+  rt_unrolled<DIST>([&](auto ic) {
+    if (decltype(ic)::value < KT) issue(decltype(ic)::value, ic);
+  });
   auto stage = [&](int kt, auto slot_c) {
     constexpr int SLOT = decltype(slot_c)::value;
-    if (kt + 1 < KT) rt_wait_vmcnt<NL>(); else rt_wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();       // stage kt landed for all waves; the slot of kt - 1 is free
+    const int later = min(DIST - 1, KT - 1 - kt);          // wave-uniform
+    rt_unrolled<DIST>([&](auto ic) {
+      if (later == decltype(ic)::value) rt_wait_vmcnt<decltype(ic)::value * NL>();
+    });
+    __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (kt + 2 < KT) issue(kt + 2, integral_constant<int, (SLOT + 2) % RT_NSTAGE>{});
+    if (kt + DIST < KT) issue(kt + DIST, integral_constant<int, (SLOT + DIST) % NS>{});
     const unsigned char* sb = smem + SLOT * L::STAGE + wrd;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -804,14 +826,11 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
       }
     }
   };
-  int kt = 0;
-  for (; kt + 2 < KT; kt += 3) {
-    stage(kt, integral_constant<int, 0>{});
-    stage(kt + 1, integral_constant<int, 1>{});
-    stage(kt + 2, integral_constant<int, 2>{});
+  for (int kt = 0; kt < KT; kt += NS) {
+    rt_unrolled<NS>([&](auto ic) {
+      if (kt + decltype(ic)::value < KT) stage(kt + decltype(ic)::value, ic);
+    });
   }
-  if (kt < KT) stage(kt, integral_constant<int, 0>{});
-  if (kt + 1 < KT) stage(kt + 1, integral_constant<int, 1>{});
 
   // ---- the partial score tiles go through LDS and come back in the selection layout: wave
   //      (ks, tile) takes tokens ks TPW .. ks TPW + TPW - 1 of its tile, LPT adjacent lanes per token,
