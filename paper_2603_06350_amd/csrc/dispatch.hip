@@ -286,8 +286,8 @@ extern "C" int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes) 
   const int nth = moe::dispatch_threads(shape->E);
   const int64_t nb = (static_cast<int64_t>(shape->T) + nth - 1) / nth;
   size_t bytes = static_cast<size_t>(nb > 0 ? nb : 1) * shape->E * sizeof(int32_t);
-  // moe_route_ws keeps T x E fp32 scores between its two kernels for batches of at most 512 tokens
-  if (shape->T <= 512) {
+  // moe_route_ws keeps T x E fp32 scores between its two kernels for small batches
+  if (shape->T <= MOE_ROUTE_WS_MAX_T) {
     const size_t route_bytes = static_cast<size_t>(shape->T) * shape->E * sizeof(float);
     if (route_bytes > bytes) bytes = route_bytes;
   }

@@ -11,6 +11,11 @@
 #define MOE_MAX_E 256
 #define MOE_MAX_K 64
 #define MOE_WAVE 64
+// moe_route_ws: largest batch whose gate product runs as a kernel of its own (T x E fp32 scores in
+// the workspace between the two kernels)
+#ifndef MOE_ROUTE_WS_MAX_T
+#define MOE_ROUTE_WS_MAX_T 2048
+#endif
 
 namespace moe {
 

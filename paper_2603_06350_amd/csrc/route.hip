@@ -930,7 +930,7 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 // gate_tile_kernel computes the fast scores of one 16-token x 16-expert tile (same arithmetic and
 // summation order as route_kernel's fast pass, so the same bits) and writes them to the buffer;
 // route_kernel<.., PRE> then selects from the buffer and runs the exact pass.
-constexpr int RT_PRE_MAX_T = 512;
+constexpr int RT_PRE_MAX_T = MOE_ROUTE_WS_MAX_T;
 
 __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,

@@ -207,7 +207,9 @@ SMALL_ROUTE_WS_CASES = [
     dict(T=32, d=4096, E=128, k=8, renorm=1),      # the decode-shaped layer's routing
     dict(T=77, d=1024, E=128, k=8, renorm=0),      # exactly 256 KB
     dict(T=130, d=2056, E=200, k=5, renorm=1),     # ragged hidden size, E > 128, E % 16 != 0
-    dict(T=512, d=2048, E=64, k=6, renorm=1),      # the largest batch that takes this path
+    dict(T=512, d=2048, E=64, k=6, renorm=1),
+    dict(T=2048, d=1024, E=128, k=8, renorm=1),    # the largest batch that takes this path
+    dict(T=2049, d=1024, E=128, k=8, renorm=1),    # one more token: one kernel again
     dict(T=1, d=4096, E=33, k=33, renorm=1),       # one token, k = E
 ]
 
@@ -219,7 +221,7 @@ def gpu_route_ws(cfg, x, w_gate, bias, with_ws, with_scores):
     w = torch.zeros((T, k), dtype=torch.float32, device="cuda")
     sc = torch.full((T, E), -3.0, dtype=torch.float32, device="cuda") if with_scores else None
     nb = B.moe_workspace_bytes(sh)
-    assert nb >= T * E * 4
+    assert nb >= T * E * 4 or T > 2048      # room for the scores of every batch that can use them
     ws = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda") if with_ws else None
     B.moe_route_ws(sh, dev(x), dev(w_gate), dev(bias), idx, w, sc, ws, nb if with_ws else 0)
     torch.cuda.synchronize()
