@@ -81,7 +81,7 @@ int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
 
 /*
  * moe_route with a device workspace (same operation, same results).  For small
- * batches (T <= 2048) with a large gate matrix the gate product is then spread over
+ * batches (T < 8192) with a large gate matrix the gate product is then spread over
  * the whole chip by a kernel of its own and the selection reads its scores from the
  * workspace; without a workspace (and without scores_out) every block has to pull
  * the whole gate matrix through one compute unit.  workspace: 16-byte aligned,

@@ -14,7 +14,7 @@
 // moe_route_ws: largest batch whose gate product runs as a kernel of its own (T x E fp32 scores in
 // the workspace between the two kernels)
 #ifndef MOE_ROUTE_WS_MAX_T
-#define MOE_ROUTE_WS_MAX_T 2048
+#define MOE_ROUTE_WS_MAX_T 8191
 #endif
 
 namespace moe {

@@ -932,47 +932,60 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 // route_kernel<.., PRE> then selects from the buffer and runs the exact pass.
 constexpr int RT_PRE_MAX_T = MOE_ROUTE_WS_MAX_T;
 
+// GNT: 16-expert tiles per block (1 for the smallest batches, 4 once there are enough token tiles
+// to fill the chip: x is then read E / 64 times instead of E / 16 times).
+template <int GNT>
 __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
     int d, int E, float* __restrict__ scores) {
-  __shared__ float part[RT_NW][RT_TM][16];
+  __shared__ float part[RT_NW][RT_TM][16 * GNT];
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
-  const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * 16;
+  const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * (16 * GNT);
   const int row16 = d / 8;
   const int r = lane & 15;   // token row of the A fragment / expert column of the B fragment
   const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
   const uint4* xrow = x + static_cast<int64_t>(min(t0 + r, T - 1)) * row16;
-  const uint4* wrow = wg + static_cast<int64_t>(min(e0 + r, E - 1)) * row16;
-  f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const uint4* wrow[GNT];
+  f32x4_t acc[GNT];
+#pragma unroll
+  for (int nt = 0; nt < GNT; ++nt) {
+    wrow[nt] = wg + static_cast<int64_t>(min(e0 + nt * 16 + r, E - 1)) * row16;
+    acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
   const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
   const int c0 = wave * cw;
   const int c1 = min(row16, c0 + cw);
   for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
-    uint4 a[RT_BATCH], b[RT_BATCH];
+    uint4 a[RT_BATCH], b[RT_BATCH][GNT];
 #pragma unroll
     for (int u = 0; u < RT_BATCH; ++u) {
       const int cc = min(cb + 4 * u + kq, row16 - 1);
       a[u] = xrow[cc];
-      b[u] = wrow[cc];
+#pragma unroll
+      for (int nt = 0; nt < GNT; ++nt) b[u][nt] = wrow[nt][cc];
     }
 #pragma unroll
     for (int u = 0; u < RT_BATCH; ++u) {
       if (cb + 4 * u < c1) {                         // wave-uniform
         uint4 av = a[u];
         if (cb + 4 * u + kq >= row16) av = make_uint4(0, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                      __builtin_bit_cast(bf16x8_t, b[u]), acc, 0, 0, 0);
+#pragma unroll
+        for (int nt = 0; nt < GNT; ++nt)
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                            __builtin_bit_cast(bf16x8_t, b[u][nt]),
+                                                            acc[nt], 0, 0, 0);
       }
     }
   }
   // D layout: lane holds expert column (lane & 15), token rows 4 * (lane >> 4) + v
 #pragma unroll
-  for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][r] = acc[v];
+  for (int nt = 0; nt < GNT; ++nt)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][nt * 16 + r] = acc[nt][v];
   __syncthreads();
-  const int tid = static_cast<int>(threadIdx.x);
-  if (tid < RT_TM * 16) {
-    const int row = tid >> 4, ee = tid & 15;
+  for (int i = static_cast<int>(threadIdx.x); i < RT_TM * 16 * GNT; i += RT_THREADS) {
+    const int row = i / (16 * GNT), ee = i % (16 * GNT);
     const int64_t t = t0 + row;
     const int e = e0 + ee;
     if (t < T && e < E) {
@@ -1023,9 +1036,15 @@ static int launch_route(const moe_shape_t* s, const void* x, const void* wg, con
     // gate product spread over the chip first, if there is somewhere to put the scores and the
     // gate matrix is large enough (256 KB: 8 us through one CU) to pay for the second launch
     if (scratch && s->T <= RT_PRE_MAX_T && static_cast<int64_t>(s->E) * s->d * 2 >= 256 * 1024) {
-      hipLaunchKernelGGL(gate_tile_kernel, dim3((s->T + RT_TM - 1) / RT_TM, (s->E + 15) / 16),
-                         dim3(RT_THREADS), 0, st, static_cast<const uint4*>(x),
-                         static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, scratch);
+      const int t_tiles = (s->T + RT_TM - 1) / RT_TM;
+      if (static_cast<int64_t>(t_tiles) * ((s->E + 63) / 64) >= 256)
+        hipLaunchKernelGGL(gate_tile_kernel<4>, dim3(t_tiles, (s->E + 63) / 64), dim3(RT_THREADS), 0, st,
+                           static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T,
+                           s->d, s->E, scratch);
+      else
+        hipLaunchKernelGGL(gate_tile_kernel<1>, dim3(t_tiles, (s->E + 15) / 16), dim3(RT_THREADS), 0, st,
+                           static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T,
+                           s->d, s->E, scratch);
       if (launch_status() != MOE_OK) return MOE_ERR_HIP;
       return launch_route_rpw<BF16, NT, 1, true>(s, x, wg, bias, idx, w, scratch, scores, tpb, st);
     }
@@ -1047,30 +1066,37 @@ static int launch_route_tile(const moe_shape_t* s, const void* x, const void* wg
   return launch_status();
 }
 
-// The large-batch path takes over when the batch fills the chip with blocks of at least two tiles
-// (the most tiles per block that still leave every CU a block; the slices of the hidden dimension
-// must be whole 64-element stages) and k and E fit its selection; returns false otherwise.
+// The large-batch path takes over when the batch gives enough blocks of at least two tiles (the
+// most tiles per block that still give that many blocks; the slices of the hidden dimension must
+// be whole 64-element stages) and k and E fit its selection; returns false otherwise.
 template <int NT>
 static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
                            int32_t* idx, float* w, float* scores, hipStream_t st, int* rc) {
-  constexpr int MIN_GRID = 256;
   if constexpr (NT > 8) {
     return false;   // more than 128 experts: a ring stage of w_gate no longer fits the LDS
   } else {
     if (s->k > RT_KSEL) return false;
     // 65 to 128 experts: only 4 tiles x 2 slices keeps both the stage and the per-lane tournament small
     constexpr int TILES_MAX = NT > 4 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
-    for (int tiles = TILES_MAX; tiles >= TILES_MIN; tiles >>= 1) {
-      if ((s->T + 16 * tiles - 1) / (16 * tiles) < MIN_GRID) continue;
-      if (s->d % (64 * (RT_NW / tiles)) != 0) continue;
-      if constexpr (NT <= 4) {
-        if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
-        if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
-      }
-      if (tiles == 4) *rc = launch_route_tile<NT, 4>(s, x, wg, bias, idx, w, scores, st);
-      return true;
+    auto blocks = [&](int tiles) { return (s->T + 16 * tiles - 1) / (16 * tiles); };
+    auto fits = [&](int tiles) { return s->d % (64 * (RT_NW / tiles)) == 0; };
+    // the most tiles per block that still give every CU a block ...
+    int tiles = 0;
+    for (int c = TILES_MAX; c >= TILES_MIN && tiles == 0; c >>= 1)
+      if (blocks(c) >= 256 && fits(c)) tiles = c;
+    // ... or, if the gate matrix is large (128 KB and more: the per-tile kernel streams all of it
+    // for every 16 tokens), the fewest tiles per block from 96 blocks on, from where this path
+    // measured faster than both other forms
+    if (tiles == 0 && static_cast<int64_t>(s->E) * s->d * 2 >= 128 * 1024 && blocks(TILES_MIN) >= 96 &&
+        fits(TILES_MIN))
+      tiles = TILES_MIN;
+    if (tiles == 0) return false;
+    if constexpr (NT <= 4) {
+      if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
+      if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
     }
-    return false;
+    if (tiles == 4) *rc = launch_route_tile<NT, 4>(s, x, wg, bias, idx, w, scores, st);
+    return true;
   }
 }
 

@@ -134,7 +134,8 @@ def test_route_near_ties_are_decided_like_the_oracle():
 
 
 # Batches large enough for the large-batch routing kernel (at least 256 blocks of 2, 4 or 8 token
-# tiles, 4 only for 65 to 128 experts; k <= 16, whole 64-element stages per slice of the hidden dimension).
+# tiles, at least 96 if the gate matrix has 128 KB or more; 4 tiles only for 65 to 128 experts;
+# k <= 16, whole 64-element stages per slice of the hidden dimension).
 # The hidden size is small so that the oracle stays fast.  T is never a multiple of the block.
 BIG_ROUTE_CASES = [
     dict(T=8195, d=256, E=64, k=6, renorm=1),      # 2 tiles per block, 4 slices
@@ -148,6 +149,8 @@ BIG_ROUTE_CASES = [
     dict(T=16400, d=256, E=128, k=8, renorm=1),    # more than 64 experts: 4 tiles per block only
     dict(T=16390, d=128, E=100, k=6, renorm=0),
     dict(T=16400, d=256, E=65, k=16, renorm=1),
+    dict(T=3100, d=2048, E=64, k=6, renorm=1),     # 256 KB gate matrix: taken from 96 blocks on
+    dict(T=6200, d=1024, E=128, k=8, renorm=0),
     dict(T=16400, d=192, E=8, k=2, renorm=1),      # slices would not be whole stages: per-tile kernel
     dict(T=8195, d=256, E=32, k=17, renorm=1),     # k too large for it: per-tile kernel
 ]
@@ -208,8 +211,8 @@ SMALL_ROUTE_WS_CASES = [
     dict(T=77, d=1024, E=128, k=8, renorm=0),      # exactly 256 KB
     dict(T=130, d=2056, E=200, k=5, renorm=1),     # ragged hidden size, E > 128, E % 16 != 0
     dict(T=512, d=2048, E=64, k=6, renorm=1),
-    dict(T=2048, d=1024, E=128, k=8, renorm=1),    # the largest batch that takes this path
-    dict(T=2049, d=1024, E=128, k=8, renorm=1),    # one more token: one kernel again
+    dict(T=2048, d=1024, E=128, k=8, renorm=1),    # enough token tiles for 64-expert gate tiles
+    dict(T=3000, d=520, E=256, k=8, renorm=0),     # more than 128 experts, ragged hidden size
     dict(T=1, d=4096, E=33, k=33, renorm=1),       # one token, k = E
 ]
 
@@ -221,7 +224,7 @@ def gpu_route_ws(cfg, x, w_gate, bias, with_ws, with_scores):
     w = torch.zeros((T, k), dtype=torch.float32, device="cuda")
     sc = torch.full((T, E), -3.0, dtype=torch.float32, device="cuda") if with_scores else None
     nb = B.moe_workspace_bytes(sh)
-    assert nb >= T * E * 4 or T > 2048      # room for the scores of every batch that can use them
+    assert nb >= T * E * 4 or T >= 8192     # room for the scores of every batch that can use them
     ws = torch.full((nb,), 0x5A, dtype=torch.uint8, device="cuda") if with_ws else None
     B.moe_route_ws(sh, dev(x), dev(w_gate), dev(bias), idx, w, sc, ws, nb if with_ws else 0)
     torch.cuda.synchronize()
