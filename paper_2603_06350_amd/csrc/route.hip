@@ -713,7 +713,7 @@ struct RouteTileLds {
   static constexpr int STAGE = ROWS * 128;
   // stages in the LDS ring (one is being read, the others are in flight): small stages move few
   // bytes each, so they need a deeper ring to keep the same number of bytes on their way from HBM
-  static constexpr int NS = STAGE <= 4096 ? 6 : (STAGE <= 8192 ? 4 : 3);
+  static constexpr int NS = STAGE <= 4096 ? 6 : (STAGE <= 8192 ? 4 : (STAGE <= 32768 ? 3 : 2));
   static constexpr int PART = RT_NW * NT * 4 * MOE_WAVE * 4;                // aliases the stages
   static constexpr int RING = NS * STAGE > PART ? NS * STAGE : PART;
   static constexpr int PICKS = RING;                        // float/int [RT_NW][2][RT_KSEL + 1][16]
@@ -721,8 +721,11 @@ struct RouteTileLds {
   static constexpr int CCOUNT = CAND + TILES * 16 * RT_CMAX * 4;            // int [16 TILES]
   static constexpr int PLIST = CCOUNT + TILES * 16 * 4;                     // int [16 TILES][RT_CMAX]
   static constexpr int FLIST = PLIST + TILES * 16 * RT_CMAX * 4;            // int [16 TILES] + two counts
-  static constexpr int DPART = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;   // double [RT_NW][max(E, RT_CMAX)]
-  static constexpr int TOTAL = DPART + RT_NW * (NT * 16 > RT_CMAX ? NT * 16 : RT_CMAX) * 8;
+  static constexpr int DPART = 0;   // double [RT_NW][max(E, RT_CMAX)]: the exact pass's partial sums also
+                                    // alias the stages (nothing there is live once the scores are read back)
+  static constexpr int TOTAL = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;
+  static_assert(RT_NW * (NT * 16 > RT_CMAX ? NT * 16 : RT_CMAX) * 8 <= RING, "exact-pass sums fit the ring");
+  static_assert(TOTAL <= 160 * 1024, "LDS of the large-batch routing kernel");
 };
 
 // Requires d % (64 KS) == 0 and k <= RT_KSEL (the host checks).
@@ -1072,11 +1075,9 @@ static int launch_route_tile(const moe_shape_t* s, const void* x, const void* wg
 template <int NT>
 static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
                            int32_t* idx, float* w, float* scores, hipStream_t st, int* rc) {
-  if constexpr (NT > 8) {
-    return false;   // more than 128 experts: a ring stage of w_gate no longer fits the LDS
-  } else {
+  {
     if (s->k > RT_KSEL) return false;
-    // 65 to 128 experts: only 4 tiles x 2 slices keeps both the stage and the per-lane tournament small
+    // more than 64 experts: only 4 tiles x 2 slices keeps both the stage and the per-lane tournament small
     constexpr int TILES_MAX = NT > 4 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
     auto blocks = [&](int tiles) { return (s->T + 16 * tiles - 1) / (16 * tiles); };
     auto fits = [&](int tiles) { return s->d % (64 * (RT_NW / tiles)) == 0; };
