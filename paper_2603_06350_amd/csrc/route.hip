@@ -1077,8 +1077,9 @@ static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, 
                            int32_t* idx, float* w, float* scores, hipStream_t st, int* rc) {
   {
     if (s->k > RT_KSEL) return false;
-    // more than 64 experts: only 4 tiles x 2 slices keeps both the stage and the per-lane tournament small
-    constexpr int TILES_MAX = NT > 4 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
+    // more than 64 experts: at least 4 tiles per block (a stage of 4 slices would not fit the ring);
+    // more than 128: exactly 4 (with 8 tiles a lane would hold 64 experts)
+    constexpr int TILES_MAX = NT > 8 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
     auto blocks = [&](int tiles) { return (s->T + 16 * tiles - 1) / (16 * tiles); };
     auto fits = [&](int tiles) { return s->d % (64 * (RT_NW / tiles)) == 0; };
     // the most tiles per block that still give every CU a block ...
@@ -1092,8 +1093,10 @@ static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, 
         fits(TILES_MIN))
       tiles = TILES_MIN;
     if (tiles == 0) return false;
-    if constexpr (NT <= 4) {
+    if constexpr (NT <= 8) {
       if (tiles == 8) *rc = launch_route_tile<NT, 8>(s, x, wg, bias, idx, w, scores, st);
+    }
+    if constexpr (NT <= 4) {
       if (tiles == 2) *rc = launch_route_tile<NT, 2>(s, x, wg, bias, idx, w, scores, st);
     }
     if (tiles == 4) *rc = launch_route_tile<NT, 4>(s, x, wg, bias, idx, w, scores, st);

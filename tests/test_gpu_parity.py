@@ -134,7 +134,7 @@ def test_route_near_ties_are_decided_like_the_oracle():
 
 
 # Batches large enough for the large-batch routing kernel (at least 256 blocks of 2, 4 or 8 token
-# tiles, at least 96 if the gate matrix has 128 KB or more; 4 tiles only for more than 64 experts;
+# tiles, at least 96 if the gate matrix has 128 KB or more; 4 or 8 tiles for 65 to 128 experts, 4 for more;
 # k <= 16, whole 64-element stages per slice of the hidden dimension).
 # The hidden size is small so that the oracle stays fast.  T is never a multiple of the block.
 BIG_ROUTE_CASES = [
@@ -149,6 +149,7 @@ BIG_ROUTE_CASES = [
     dict(T=16400, d=256, E=128, k=8, renorm=1),    # more than 64 experts: 4 tiles per block only
     dict(T=16390, d=128, E=100, k=6, renorm=0),
     dict(T=16400, d=256, E=65, k=16, renorm=1),
+    dict(T=32800, d=128, E=100, k=6, renorm=1),    # 8 tiles per block with more than 64 experts
     dict(T=16400, d=256, E=256, k=8, renorm=1),    # the most experts the library takes
     dict(T=16390, d=128, E=200, k=6, renorm=0),
     dict(T=3100, d=2048, E=64, k=6, renorm=1),     # 256 KB gate matrix: taken from 96 blocks on
@@ -167,7 +168,8 @@ def test_route_large_batch_matches_oracle(case):
     check_route(cfg, L["x"], L["w_gate"], bias)
 
 
-@pytest.mark.parametrize("T,E", [(8195, 32), (16400, 32), (32800, 32), (16400, 128), (16400, 256)])
+@pytest.mark.parametrize("T,E", [(8195, 32), (16400, 32), (32800, 32), (16400, 128), (32800, 128),
+                                 (16400, 256)])
 def test_route_large_batch_ties_and_near_ties(T, E):
     # duplicated gate rows (exact ties), all-zero tokens (every score equal: more candidates than
     # the exact pass lists, so all experts are re-scored), a 1e-6 bias between two equal rows
