@@ -8,15 +8,17 @@
 // Two GEMMs: a gated one (W1 and W3 tiles side by side, SwiGLU applied to the fp32
 // accumulators, h stored once) and a plain one for W2.  Both are ragged grouped
 // GEMMs: the tile list is derived on the device from `offsets`, so the host never
-// learns the expert loads.  Each GEMM is two launches over disjoint tile lists:
-//   main   block tile BM x 256 weight rows (BM = 256 or 128): every full tile of an
-//          expert's segment, and its remainder if that has more than 64 rows;
-//   small  block tile 64 x 256: remainders of at most 64 rows (the tail of a large
-//          expert, or all of a small one: decode-shaped layers live here).
+// learns the expert loads.  With 128 or more rows per expert on average each GEMM is two
+// launches over disjoint tile lists:
+//   main   block tile 256 x 256 weight rows: every full tile of an expert's segment,
+//          and its remainder if that has more than 64 rows;
+//   small  block tile 64 x 256: remainders of at most 64 rows.
 // A small tile has little arithmetic per weight byte, so it is paced by memory
-// latency: it runs a four-stage LDS ring with three stages of loads in flight.  For
-// layers with large experts the small launches run on a side stream next to the main
-// ones (they stream weights from HBM while the main tiles are MFMA/L2 bound).
+// latency: it runs a four-stage LDS ring with three stages of loads in flight.  The
+// small launches run on a side stream next to the main ones (they stream weights from
+// HBM while the main tiles are MFMA/L2 bound).  Below 128 rows per expert (decode and
+// small prefill batches: the call is bound by streaming the weights once) every segment
+// is cut into 64-row ring tiles, one launch per GEMM.
 //
 // bf16 kernels (gfx950): 512 threads = 8 waves, two per SIMD.  K step 64: both
 // operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
@@ -689,22 +691,16 @@ static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
   return launch_status();
 }
 
-// 256-row main tiles once the mean rows per expert reach 192: an expert with about one tile's
-// worth of rows is then one (partial) tile instead of a 128-row tile plus a remainder that would
-// stream its weights a second time.
-static bool big_tiles(const GemmArgs& g, int64_t A) { return A / g.E >= 192; }
-
 // Main tiles of one grouped GEMM on the MFMA path.
 template <bool GATED>
 static int mfma_gemm_main(const GemmArgs& g, int64_t A, hipStream_t st) {
-  return big_tiles(g, A) ? launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st)
-                         : launch_mfma<128, GATED, 2, 4, 2>(g, TILES_MAIN, 128, A, st);
+  return launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st);
 }
 
 // The small remainders of the same GEMM.
 template <bool GATED>
 static int mfma_gemm_small(const GemmArgs& g, int64_t A, hipStream_t st) {
-  return launch_mfma<64, GATED, 2, 4, 4>(g, TILES_SMALL, big_tiles(g, A) ? 256 : 128, A, st);
+  return launch_mfma<64, GATED, 2, 4, 4>(g, TILES_SMALL, 256, A, st);
 }
 
 // The remainder launches stream whole weight matrices from HBM for a few rows each, while the
@@ -740,24 +736,13 @@ static SideStream* side_stream_locked() {
 static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, int64_t A,
                     hipStream_t st) {
   int rc = MOE_OK;
-  // Overlap pays when the main launches are long; decode-shaped calls stay on one stream.
-  const bool overlap = A / g1.E >= 128;
-  if (A / g1.E < 16) {
-    // a handful of rows per expert (decode-shaped calls): everything as 64-row tiles in one launch
-    // per GEMM; a main launch would find no tile and only cost its start-up
+  if (A / g1.E < 128) {
+    // Few rows per expert (decode, small prefill batches): the call is bound by streaming each
+    // expert's weights once, which the latency-hiding ring of the 64-row tiles does best, and a
+    // 256-row tile would be mostly padding.  One launch per GEMM.  (Measured at the Mixtral
+    // shape: 64 rows per expert 0.85 -> 0.63 ms against 128-row main tiles plus remainders.)
     if (up && (rc = launch_mfma<64, true, 2, 4, 4>(g1, TILES_ALL, 64, A, st)) != MOE_OK) return rc;
     if (down) rc = launch_mfma<64, false, 2, 4, 4>(g2, TILES_ALL, 64, A, st);
-    return rc;
-  }
-  if (!overlap) {
-    if (up) {
-      if ((rc = mfma_gemm_main<true>(g1, A, st)) != MOE_OK) return rc;
-      if ((rc = mfma_gemm_small<true>(g1, A, st)) != MOE_OK) return rc;
-    }
-    if (down) {
-      if ((rc = mfma_gemm_main<false>(g2, A, st)) != MOE_OK) return rc;
-      if ((rc = mfma_gemm_small<false>(g2, A, st)) != MOE_OK) return rc;
-    }
     return rc;
   }
   std::lock_guard<std::mutex> lock(g_side_mutex);

@@ -378,7 +378,8 @@ def check_ffn(cfg, L, idx):
 
 
 FFN_CASES = [
-    dict(T=300, d=256, E=8, k=2, F=384),          # MFMA path, 128-row tiles, ragged
+    dict(T=300, d=256, E=8, k=2, F=384),          # MFMA path, 75 rows/expert: 64-row tiles only, ragged
+    dict(T=600, d=256, E=8, k=2, F=384),          # 150 rows/expert: partial 256-row tiles + remainders
     dict(T=1500, d=128, E=2, k=1, F=256),         # MFMA path, 256-row tiles (>= 512 rows/expert)
     dict(T=900, d=192, E=3, k=2, F=320),          # 256-row tiles, N tails (320 = 2.5 x 128, 192 < 256)
     dict(T=64, d=512, E=64, k=6, F=128),          # many small / empty experts
@@ -389,8 +390,8 @@ FFN_CASES = [
 
 
 def test_grouped_ffn_few_rows_per_expert_with_one_hot_expert():
-    # fewer than 16 rows per expert on average (everything runs as 64-row tiles in one launch per
-    # GEMM), but one expert holds several tiles' worth of rows and most are empty
+    # few rows per expert on average (everything runs as 64-row tiles in one launch per GEMM),
+    # but one expert holds several tiles' worth of rows and most are empty
     cfg = si.small_config(T=400, d=256, E=64, k=1, F=384)
     L = si.make_layer(cfg)
     rng = np.random.default_rng(5)
