@@ -20,6 +20,9 @@
 // small prefill batches: the call is bound by streaming the weights once) every segment
 // is cut into 64-row ring tiles, one launch per GEMM.
 //
+// The main tile keeps its operands in a ring of five 32 KiB half-stage slots (all of the CU's LDS):
+// two are being multiplied, up to three are in flight.
+//
 // bf16 kernels (gfx950): 512 threads = 8 waves, two per SIMD.  K step 64: both
 // operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
 // global -> LDS with 16-byte-per-lane buffer loads that write LDS directly (no register
@@ -243,8 +246,15 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 #undef MOE_VMCNT_CASE
 }
 
+// The two-stage form (NSTAGE == 2) keeps its operands in a ring of five half-stage slots (see the
+// full-tile path of the kernel), which needs equally large activation and weight halves.
+constexpr bool ffn_half_ring(int bm, int nstage) { return nstage == 2 && bm == BROWS; }
+constexpr int ffn_lds_bytes(int bm, int nstage) {
+  return ffn_half_ring(bm, nstage) ? 5 * bm * ROWB : nstage * (bm + BROWS) * ROWB;
+}
+
 // BM x 256 block tile, WM x WN waves, NSTAGE LDS stages of 64 K-elements.
-// NSTAGE == 2: hand-ordered double-buffered pipeline (large tiles, MFMA/L2 bound).
+// NSTAGE == 2: hand-ordered pipeline (large tiles, MFMA/L2 bound).
 // NSTAGE  > 2: ring with NSTAGE-1 stages of loads in flight (small tiles, latency bound).
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
@@ -260,6 +270,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int BN_OUT = GATED ? 128 : 256;       // output columns per block tile
   static_assert(NLA * 8 * NW == BM && NLB * 8 * NW == 128 && MI >= 1 && NIH >= 1, "tile shape");
   static_assert(KSTEPS == 2, "the pipelines below are written for two k-steps per stage");
+  static_assert(NSTAGE > 2 || ffn_half_ring(BM, NSTAGE), "NSTAGE == 2 means the half-stage ring");
   extern __shared__ __align__(1024) unsigned char lds[];
 
   TileCoord tc;
@@ -315,12 +326,15 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
       __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_b0), 0, 0x7FFFFFFF, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<unsigned char*>(GATED ? base_b1 : base_b0), 0, 0x7FFFFFFF, 0x00020000);
-  auto issue_load = [&](int i, int kt, int stage) {
-    const int g = i * NW + wave;
+  // instruction i of stage kt, written to LDS byte offset dst (1 KiB per wave instruction)
+  auto issue_load_at = [&](int i, int kt, int dst) {
     const __amdgpu_buffer_rsrc_t rs = (i < NLA) ? rs_a : (!GATED || i < NLA + NLB) ? rs_b0 : rs_b1;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(
-        rs, (__attribute__((address_space(3))) void*)(lds + stage * STAGE + g * 1024), 16,
+        rs, (__attribute__((address_space(3))) void*)(lds + dst), 16,
         static_cast<int>(soff[i]), kt * ROWB, 0, 0);
+  };
+  auto issue_load = [&](int i, int kt, int stage) {
+    issue_load_at(i, kt, stage * STAGE + (i * NW + wave) * 1024);
   };
 
   // ---- LDS read addresses of the MFMA fragments ------------------------------------------------
@@ -350,18 +364,19 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
       for (int v = 0; v < 4; ++v) acc[ni][mi][v] = 0.f;
 
   // compiler-scheduled stage: used for partial tiles and by the ring pipeline
-  auto compute_guarded = [&](int stage) {
-    const unsigned char* sb = lds + stage * STAGE;
+  auto compute_at = [&](int off_a, int off_w) {
+    const unsigned char* sa = lds + off_a;
+    const unsigned char* sw = lds + off_w - BM * ROWB;    // w_base counts rows from the stage's first
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
       bf16x8_t xf[MI], wf[NI];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
         if (mi < mi_valid)
-          xf[mi] = *reinterpret_cast<const bf16x8_t*>(sb + x_base + mi * 16 * ROWB + koff[kk]);
+          xf[mi] = *reinterpret_cast<const bf16x8_t*>(sa + x_base + mi * 16 * ROWB + koff[kk]);
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
-        wf[ni] = *reinterpret_cast<const bf16x8_t*>(sb + w_base + w_sub(ni) * ROWB + koff[kk]);
+        wf[ni] = *reinterpret_cast<const bf16x8_t*>(sw + w_base + w_sub(ni) * ROWB + koff[kk]);
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
@@ -370,6 +385,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
             acc[ni][mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ni], xf[mi], acc[ni][mi], 0, 0, 0);
     }
   };
+  auto compute_guarded = [&](int stage) { compute_at(stage * STAGE, stage * STAGE + BM * ROWB); };
 
   if constexpr (NSTAGE > 2) {
     // ---- ring pipeline: the loads of stage kt+DIST are issued at the start of stage kt -------
@@ -395,113 +411,171 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
       if (mi_valid > 0) compute_guarded(kt % NSTAGE);
     }
   } else if (mi_valid < MI) {
-    // ---- two stages, partial tile: same barrier protocol as the full path below ----------------
+    // ---- partial tile in the ring of five half-stage slots: the loads, slots and barriers of the
+    //      full-tile path below (waves of one block take either path), compiler-scheduled MFMAs
+    constexpr int HALF = BM * ROWB;
+    auto issue_act = [&](int kt, int slot) {
 #pragma unroll
-    for (int i = 0; i < NLOAD; ++i) issue_load(i, 0, 0);
-    wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    for (int kt = 0; kt < KT; ++kt) {
-      if (kt + 1 < KT) {
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) issue_load(i, kt + 1, (kt + 1) & 1);
-      }
-      if (mi_valid > 0) compute_guarded(kt & 1);
-      wait_vmcnt<0>();
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-    }
-  } else {
-    // ---- two stages, full tile: hand-ordered pipeline --------------------------------------------
-    // A stage holds two k-steps (32 K-elements each).  Weight fragments live in ONE register set:
-    // as soon as the MFMAs that use w[ni] have been issued, w[ni] is re-read for the next k-step,
-    // so every LDS read has a whole k-step of MFMAs (its own wave's and the SIMD's other wave's)
-    // to land.  Activation fragments alternate between two sets.  LDS reads return in order, so
-    // "the fragment I need has landed" is s_waitcnt lgkmcnt(reads issued after it) = NI + MI - 1.
-    //
-    // The stage's one barrier sits between its two k-steps.  Before it a wave waits for its own
-    // global->LDS loads of stage kt+1 and for its last LDS reads of buffer CUR; after it, buffer
-    // CUR^1 may be read (first fragments of stage kt+1, fetched while k-step 1 multiplies) and
-    // buffer CUR may be overwritten (loads of stage kt+2, issued at once).  Inline asm pins
-    // the order; the compiler does not see these LDS reads, so it inserts no waits of its own.
-    int xad[2][KSTEPS], wad[2][KSTEPS];       // per stage buffer, per k-step LDS byte addresses
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int kk = 0; kk < KSTEPS; ++kk) {
-        xad[st][kk] = st * STAGE + x_base + koff[kk];
-        wad[st][kk] = st * STAGE + w_base + koff[kk];
-      }
-    bf16x8_t xA[MI], xB[MI], wf[NI];
-    constexpr int PEND = NI + MI - 1;
-    static_assert(PEND <= 15, "lgkmcnt immediate");
-#define MOE_RD(dst, addr, off) \
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
-#define MOE_MFMA(c, w, x) \
-  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
-#define MOE_W_OFF(ni) ((GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
-    auto read_x = [&](bf16x8_t (&xf)[MI], int xa) {
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) MOE_RD(xf[mi], xa, mi * 16 * ROWB);
+      for (int j = 0; j < NLA; ++j) issue_load_at(j, kt, slot * HALF + (j * NW + wave) * 1024);
     };
-    auto stage_body = [&](int kt, auto cur_c) {
-      constexpr int CUR = decltype(cur_c)::value;
-      const bool more2 = kt + 2 < KT;               // wave-uniform
-      // k-step 0 multiplies (wf, xA) and fetches k-step 1's fragments
-      read_x(xB, xad[CUR][1]);
+    auto issue_wgt = [&](int kt, int slot) {
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        asm volatile("s_waitcnt lgkmcnt(%0)" ::"i"(PEND) : "memory");
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xA[mi]);
-        MOE_RD(wf[ni], wad[CUR][1], MOE_W_OFF(ni));
-      }
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");
-      // Buffer CUR is free: the loads of stage kt+2 go out at once (they have exactly one stage
-      // to land, and every cycle earlier counts).
-      if (more2) {
-#pragma unroll
-        for (int i = 0; i < NLOAD; ++i) issue_load(i, kt + 2, CUR);
-      }
-      // k-step 1 multiplies (wf, xB): all it needs has landed.  The fragment reads below fetch
-      // the first k-step of stage kt+1; after the last stage they read stale LDS and go unused.
-      read_x(xA, xad[CUR ^ 1][0]);
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xB[mi]);
-        MOE_RD(wf[ni], wad[CUR ^ 1][0], MOE_W_OFF(ni));
-      }
+      for (int j = 0; j < NLA; ++j) issue_load_at(NLA + j, kt, slot * HALF + (j * NW + wave) * 1024);
     };
-    using T0 = std::integral_constant<int, 0>;
-    using T1 = std::integral_constant<int, 1>;
-
-#pragma unroll
-    for (int i = 0; i < NLOAD; ++i) issue_load(i, 0, 0);
+    issue_act(0, 0);
+    issue_wgt(0, 1);
     if (KT > 1) {
-#pragma unroll
-      for (int i = 0; i < NLOAD; ++i) issue_load(i, 1, 1);
-      wait_vmcnt<NLOAD>();
+      issue_act(1, 2);
+      issue_wgt(1, 3);
+    }
+    if (KT > 2) {
+      issue_act(2, 4);
+      wait_vmcnt<3 * NLA>();
+    } else if (KT > 1) {
+      wait_vmcnt<2 * NLA>();
     } else {
       wait_vmcnt<0>();
     }
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    read_x(xA, xad[0][0]);
-#pragma unroll
-    for (int ni = 0; ni < NI; ++ni) MOE_RD(wf[ni], wad[0][0], MOE_W_OFF(ni));
-    int kt = 0;
-    for (; kt + 1 < KT; kt += 2) {
-      stage_body(kt, T0{});
-      stage_body(kt + 1, T1{});
+    int slot_a = 0;                                 // slot of A(kt); W(kt) sits in the next one
+    for (int kt = 0; kt < KT; ++kt) {
+      const int slot_w = slot_a == 4 ? 0 : slot_a + 1;
+      if (mi_valid > 0) compute_at(slot_a * HALF, slot_w * HALF);
+      if (kt + 2 < KT) wait_vmcnt<NLA>();           // A(kt+2) may still fly
+      else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (kt + 2 < KT) issue_wgt(kt + 2, slot_a);
+      if (kt + 3 < KT) issue_act(kt + 3, slot_w);
+      slot_a = slot_w == 4 ? 0 : slot_w + 1;
     }
-    if (kt < KT) stage_body(kt, T0{});
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the unused reads of the last stage
-    // the compiler's hazard handling does not see asm MFMAs: let the last results retire
-    // before ordinary VALU code reads the accumulators
-    asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+  } else {
+#define MOE_RD(dst, addr, off) \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
+#define MOE_MFMA(c, w, x) \
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
+#define MOE_W_OFF(ni) ((GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
+    {
+      // ---- full tile, ring of five half-stage slots: hand-ordered pipeline -----------------------
+      // A stage is two halves of 32 KiB, the activation rows A(kt) and the weight rows W(kt); half
+      // number h = 2*kt (A) or 2*kt + 1 (W) lives in slot h % 5 of a 160 KiB ring.  Two slots are
+      // being multiplied, and up to three halves are in flight: the L2 delivers more to a CU that
+      // keeps more requests outstanding, and a plain double buffer has at most one stage in flight
+      // and none at each barrier.
+      //
+      // A stage holds two k-steps (32 K-elements each).  Weight fragments live in ONE register
+      // set: as soon as the MFMAs that use w[ni] have been issued, w[ni] is re-read for the next
+      // k-step, so every LDS read has a whole k-step of MFMAs (its own wave's and the SIMD's other
+      // wave's) to land.  Activation fragments alternate between two sets.  LDS reads return in
+      // order, so "the fragment I need has landed" is s_waitcnt lgkmcnt(reads issued after it) =
+      // NI + MI - 1.  Inline asm pins the order; the compiler does not see these LDS reads, so it
+      // inserts no waits of its own.
+      // The stage's one barrier sits between its two k-steps.  Before the barrier of stage kt a
+      // wave waits until its own loads of W(kt+1) have landed (A(kt+2), issued after them, may
+      // still fly) and for its last LDS reads of the stage's two slots; after it, those two slots
+      // take W(kt+2) and A(kt+3), and the fragments of stage kt+1 may be read.
+      static_assert(BM == BROWS && NLA == 2 * NLB, "halves of equal size");
+      constexpr int HALF = BM * ROWB;
+      constexpr int NSLOT = 5;
+      static_assert(NSLOT * HALF == ffn_lds_bytes(BM, NSTAGE), "ring size");
+      // LDS byte addresses of this lane's fragments: per pair of slots (the slot's parity goes into
+      // the instruction's 16-bit offset), per k-step
+      int xad[3][KSTEPS], wad[3][KSTEPS];
+#pragma unroll
+      for (int pr = 0; pr < 3; ++pr)
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+          xad[pr][kk] = pr * 2 * HALF + x_base + koff[kk];
+          wad[pr][kk] = pr * 2 * HALF + (w_base - BM * ROWB) + koff[kk];
+        }
+      static_assert(HALF + MOE_W_OFF(NI - 1) < 65536 && HALF + (MI - 1) * 16 * ROWB < 65536,
+                    "ds_read offset field");
+      bf16x8_t xA[MI], xB[MI], wf[NI];
+      constexpr int PEND = NI + MI - 1;
+      static_assert(PEND <= 15, "lgkmcnt immediate");
+      // the wave's NLA instructions of one half of stage kt into `slot`
+      auto issue_half = [&](auto weights_c, int kt, auto slot_c) {
+        constexpr int FIRST = decltype(weights_c)::value ? NLA : 0;
+        constexpr int SLOT = decltype(slot_c)::value;
+#pragma unroll
+        for (int j = 0; j < NLA; ++j)
+          issue_load_at(FIRST + j, kt, SLOT * HALF + (j * NW + wave) * 1024);
+      };
+      using ActHalf = std::false_type;
+      using WgtHalf = std::true_type;
+      auto stage_body = [&](int kt, auto phase_c) {
+        constexpr int PH = decltype(phase_c)::value;            // kt % 5
+        constexpr int SA = (2 * PH) % NSLOT, SW = (2 * PH + 1) % NSLOT;        // this stage's slots
+        constexpr int NA = (2 * PH + 2) % NSLOT, NWT = (2 * PH + 3) % NSLOT;   // the next stage's
+        // k-step 0 multiplies (wf, xA) and fetches k-step 1's fragments
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) MOE_RD(xB[mi], xad[SA / 2][1], (SA & 1) * HALF + mi * 16 * ROWB);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          asm volatile("s_waitcnt lgkmcnt(%0)" ::"i"(PEND) : "memory");
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xA[mi]);
+          MOE_RD(wf[ni], wad[SW / 2][1], (SW & 1) * HALF + MOE_W_OFF(ni));
+        }
+        if (kt + 2 < KT)                                        // wave-uniform: A(kt+2) is in flight
+          asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"i"(NLA) : "memory");
+        else
+          asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        // this stage's slots are free (their last fragments sit in registers)
+        if (kt + 2 < KT) issue_half(WgtHalf{}, kt + 2, std::integral_constant<int, SA>{});
+        if (kt + 3 < KT) issue_half(ActHalf{}, kt + 3, std::integral_constant<int, SW>{});
+        // k-step 1 multiplies (wf, xB) and fetches the first fragments of stage kt+1; after the
+        // last stage these reads return stale LDS and go unused
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) MOE_RD(xA[mi], xad[NA / 2][0], (NA & 1) * HALF + mi * 16 * ROWB);
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+          for (int mi = 0; mi < MI; ++mi) MOE_MFMA(acc[ni][mi], wf[ni], xB[mi]);
+          MOE_RD(wf[ni], wad[NWT / 2][0], (NWT & 1) * HALF + MOE_W_OFF(ni));
+        }
+      };
+      // prologue: A(0), W(0), A(1), W(1), A(2) in this order; stage 0 must have landed
+      issue_half(ActHalf{}, 0, std::integral_constant<int, 0>{});
+      issue_half(WgtHalf{}, 0, std::integral_constant<int, 1>{});
+      if (KT > 1) {
+        issue_half(ActHalf{}, 1, std::integral_constant<int, 2>{});
+        issue_half(WgtHalf{}, 1, std::integral_constant<int, 3>{});
+      }
+      if (KT > 2) {
+        issue_half(ActHalf{}, 2, std::integral_constant<int, 4>{});
+        wait_vmcnt<3 * NLA>();
+      } else if (KT > 1) {
+        wait_vmcnt<2 * NLA>();
+      } else {
+        wait_vmcnt<0>();
+      }
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) MOE_RD(xA[mi], xad[0][0], mi * 16 * ROWB);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) MOE_RD(wf[ni], wad[0][0], HALF + MOE_W_OFF(ni));
+      int kt = 0;
+      for (; kt + NSLOT <= KT; kt += NSLOT) {
+        stage_body(kt, std::integral_constant<int, 0>{});
+        stage_body(kt + 1, std::integral_constant<int, 1>{});
+        stage_body(kt + 2, std::integral_constant<int, 2>{});
+        stage_body(kt + 3, std::integral_constant<int, 3>{});
+        stage_body(kt + 4, std::integral_constant<int, 4>{});
+      }
+      if (kt < KT) stage_body(kt, std::integral_constant<int, 0>{});
+      if (kt + 1 < KT) stage_body(kt + 1, std::integral_constant<int, 1>{});
+      if (kt + 2 < KT) stage_body(kt + 2, std::integral_constant<int, 2>{});
+      if (kt + 3 < KT) stage_body(kt + 3, std::integral_constant<int, 3>{});
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the unused reads of the last stage
+      // the compiler's hazard handling does not see asm MFMAs: let the last results retire
+      // before ordinary VALU code reads the accumulators
+      asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+    }
 #undef MOE_RD
 #undef MOE_MFMA
 #undef MOE_W_OFF
@@ -519,7 +593,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int PITCH = CW * 2 + 32;              // bytes
   constexpr int LPR = CW * 2 / 16;                // lanes that store one row
   constexpr int RPI = 64 / LPR;                   // rows per store instruction
-  static_assert(16 % RPI == 0 && NW * 16 * PITCH <= NSTAGE * STAGE, "epilogue staging");
+  static_assert(16 % RPI == 0 && NW * 16 * PITCH <= ffn_lds_bytes(BM, NSTAGE), "epilogue staging");
   unsigned char* region = lds + wave * (16 * PITCH);
   bf16_t* out = static_cast<bf16_t*>(p.out);
   const int col0 = n0 + wn * CW;                  // first output column of this wave
@@ -663,7 +737,7 @@ static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
 
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 static int launch_mfma(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t st) {
-  constexpr int lds_bytes = NSTAGE * (BM + BROWS) * ROWB;
+  constexpr int lds_bytes = ffn_lds_bytes(BM, NSTAGE);
   static LdsOnce once;
   if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>),
                          lds_bytes) != MOE_OK)

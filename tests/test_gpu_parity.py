@@ -409,6 +409,21 @@ def test_grouped_ffn_matches_oracle(case):
     check_ffn(cfg, L, idx)
 
 
+@pytest.mark.parametrize("d,F", [(64, 704), (128, 640), (192, 576), (256, 512), (320, 448), (384, 384)])
+def test_grouped_ffn_every_stage_count_of_the_main_tile_ring(d, F):
+    # K stages of 64 elements: the up-projection takes d / 64 of them and the down-projection F / 64,
+    # so the six cases run the main tile's five-slot operand ring over 1 to 11 stages (prologue only,
+    # every tail length, several turns of the ring); each expert has full 256-row tiles, one partial
+    # main tile whose waves take the other code path of the same block, or a small remainder
+    cfg = si.small_config(T=1000, d=d, E=3, k=1, F=F)
+    L = si.make_layer(cfg)
+    idx = np.zeros((cfg.T, 1), dtype=np.int32)
+    idx[:256] = 0            # exactly one full tile
+    idx[256:256 + 300] = 1   # one full tile and a small remainder (44 rows)
+    idx[556:] = 2            # one full tile and a partial main tile (188 rows)
+    check_ffn(cfg, L, idx)
+
+
 def test_grouped_ffn_skewed_and_empty_experts():
     cfg = si.small_config(T=700, d=128, E=8, k=2, F=256)
     L = si.make_layer(cfg)
