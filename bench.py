@@ -78,6 +78,9 @@ def main():
     ap.add_argument("--materialize-x-perm", action="store_true",
                     help="write the permuted activations and run the FFN on them (the four-call form); "
                          "default: the up-projection reads x through the permutation map")
+    ap.add_argument("--ep-sim", type=int, default=0, metavar="G",
+                    help="also report the expert-parallel latency model for G simulated GPUs: every "
+                         "rank's grouped FFN run alone, static placement against Algorithms 1 + 2")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -279,6 +282,14 @@ def main():
     }
     if consumers is not None:
         out["load_consumers"] = consumers
+    if args.ep_sim > 0:
+        # outside the timed region: the permuted rows are materialised once, then every simulated
+        # rank's grouped FFN runs alone
+        from paper_2603_06350_amd import ep_sim
+        B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
+        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
+                                buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
+        out["ep_simulation"] = ep_sim.simulate(buf, x, w1, w3, w2, args.ep_sim)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, L, CPU_SAMPLE_TOKENS.get(cfg.name, min(cfg.T, 256)))
     print(json.dumps(out))
