@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--ep-sim", type=int, default=0, metavar="G",
                     help="also report the expert-parallel latency model for G simulated GPUs: every "
                          "rank's grouped FFN run alone, static placement against Algorithms 1 + 2")
+    ap.add_argument("--predictor-accuracy", action="store_true",
+                    help="also report how the loads predicted from x match those the same gate gives "
+                         "on x + eps * noise (a residual-stream stand-in), for several eps")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -282,6 +285,28 @@ def main():
     }
     if consumers is not None:
         out["load_consumers"] = consumers
+    if args.predictor_accuracy:
+        import numpy as np
+        w_acc = layer.to_device(si.make_layer(
+            si.small_config("predictor_gate", T=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, F=cfg.F,
+                            dtype=cfg.dtype, renorm=cfg.renorm, seed=cfg.seed + 1),
+            parts=("w_gate",))["w_gate"])
+        p_acc = layer.LoadPredictor(cfg.T, cfg.d, cfg.E, cfg.k, cfg.dtype, cfg.renorm, cfg.E)
+        rows = []
+        for eps in (0.0, 0.1, 0.25, 0.5, 1.0):
+            x_later = layer.to_device(si.residual_step(cfg, L["x"], eps))
+            cp, ca, same = layer.predicted_vs_actual_loads(p_acc, x, x_later, w_acc, bias, st)
+            cp, ca = cp.astype(np.float64), ca.astype(np.float64)
+            r = float(np.corrcoef(cp, ca)[0, 1]) if cp.std() > 0 and ca.std() > 0 else 1.0
+            rows.append({"eps": eps, "pearson_r_of_counts": r,
+                         "mean_abs_count_error_over_mean_count": float(np.abs(cp - ca).mean() / ca.mean()),
+                         "max_abs_count_error_over_max_count": float(np.abs(cp - ca).max() / ca.max()),
+                         "token_choices_kept": same})
+        out["predictor_accuracy"] = {
+            "model": "x_later = x + eps * N(0,1) per element (x ~ N(0,1)); the predictor is the later "
+                     "layer's gate (a second seeded gate matrix) applied to x, the truth the same gate "
+                     "on x_later; the workload's gate bias is applied to both",
+            "rows": rows}
     if args.ep_sim > 0:
         # outside the timed region: the permuted rows are materialised once, then every simulated
         # rank's grouped FFN runs alone

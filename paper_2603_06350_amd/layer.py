@@ -134,3 +134,21 @@ class LoadPredictor:
                                  self.max_segments, self.gpu_of[cur], self.gpu_load, self.gpu_count,
                                  self.n_warm, s)
             self.round += 1
+
+
+def predicted_vs_actual_loads(pred: LoadPredictor, x_now, x_later, w_pred, gate_bias=None, stream=None):
+    """How well the loads predicted from the current hidden states match those the same gate sees
+    one layer later (paper, Section 4.1 and its accuracy study): both passes are the library's
+    routing and counting; the comparison of the two small count vectors is host arithmetic.
+    Returns (predicted counts, actual counts, fraction of (token, slot) choices that the later
+    routing also makes for that token)."""
+    s = torch.cuda.current_stream() if stream is None else stream
+    pred.enqueue(x_now, w_pred, gate_bias, stream=s)
+    with torch.cuda.stream(s):
+        c_pred = pred.counts.clone()
+        idx_pred = pred.topk_idx.clone()
+    pred.enqueue(x_later, w_pred, gate_bias, stream=s)
+    with torch.cuda.stream(s):
+        same = (idx_pred.unsqueeze(2) == pred.topk_idx.unsqueeze(1)).any(dim=2).float().mean()
+    s.synchronize()
+    return c_pred.cpu().numpy(), pred.counts.cpu().numpy(), float(same.item())

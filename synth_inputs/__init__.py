@@ -176,6 +176,18 @@ def make_layer(cfg: LayerConfig, parts=("x", "w_gate", "w1", "w3", "w2"), worker
     return out
 
 
+def residual_step(cfg: LayerConfig, x: np.ndarray, eps: float, step: int = 1) -> np.ndarray:
+    """The hidden states one layer later under a residual-stream model: x + eps * x_std * n with
+    n ~ N(0, 1) drawn from the child seed [seed, 5, step], stored in the layer's dtype.  Stands in
+    for the slowly varying hidden states that make a later layer's gate usable as a predictor
+    (paper, Section 4.1); eps is the relative size of one layer's update."""
+    x_std = cfg.x_std if cfg.x_std > 0 else 1.0
+    x32 = x if cfg.dtype == F32 else bf16_bits_to_f32(x)
+    rng = np.random.default_rng([cfg.seed, 5, int(step)])
+    n = rng.standard_normal(x32.shape, dtype=np.float32)
+    return _store(x32 + np.float32(eps * x_std) * n, cfg.dtype)
+
+
 def expert_weights(cfg: LayerConfig, e: int):
     """(w1_e [F,d], w3_e [F,d], w2_e [d,F]) of one expert, drawn alone."""
     w_std = cfg.w_std if cfg.w_std > 0 else 1.0 / math.sqrt(cfg.d)

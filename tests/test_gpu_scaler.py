@@ -157,6 +157,32 @@ def test_replica_segments_matches_oracle_and_respects_the_bound():
             assert np.all(who.cpu().numpy()[m:max_seg] == -9)
 
 
+def test_predicted_and_later_loads_on_a_residual_stream_match_the_oracle():
+    """Section 4.1: the loads predicted from the current hidden states against the loads the same
+    gate produces one layer later (stand-in: x + eps * noise).  Both count vectors and the share of
+    token choices that survive are the oracle's on the same input bytes; eps = 0 predicts exactly."""
+    cfg = si.small_config("pred_acc", T=900, d=256, E=16, k=2, F=64, zipf_alpha=1.2, zipf_scale=0.5)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    bias = L["gate_bias"]
+    w_pred = si.make_layer(si.small_config("pred_gate", T=cfg.T, d=cfg.d, E=cfg.E, k=cfg.k, F=64,
+                                           seed=cfg.seed + 1), parts=("w_gate",))["w_gate"]
+    pred = layer.LoadPredictor(cfg.T, cfg.d, cfg.E, cfg.k, cfg.dtype, cfg.renorm, max_extra_replicas=8)
+    x_dev, w_dev, b_dev = layer.to_device(L["x"]), layer.to_device(w_pred), layer.to_device(bias)
+    for eps in (0.0, 0.5):
+        x_later = si.residual_step(cfg, L["x"], eps)
+        cp, ca, kept = layer.predicted_vs_actual_loads(pred, x_dev, layer.to_device(x_later), w_dev, b_dev)
+        idx_now, _, _ = orc.route(L["x"], w_pred, cfg.k, cfg.renorm, bias)
+        idx_later, _, _ = orc.route(x_later, w_pred, cfg.k, cfg.renorm, bias)
+        assert np.array_equal(cp, np.bincount(idx_now.ravel(), minlength=cfg.E))
+        assert np.array_equal(ca, np.bincount(idx_later.ravel(), minlength=cfg.E))
+        kept_ref = np.mean([[idx_now[t, j] in idx_later[t] for j in range(cfg.k)] for t in range(cfg.T)])
+        assert abs(kept - kept_ref) < 1e-6
+        if eps == 0.0:
+            assert np.array_equal(cp, ca) and kept == 1.0
+        else:
+            assert 0.3 < kept < 1.0 and not np.array_equal(cp, ca)
+
+
 def test_predictor_on_a_side_stream_next_to_the_layer():
     """Section 4.1 / 5: the gate of a later layer (here: a second seeded gate matrix; fine-tuning is
     out of scope) scores the current layer's input on a side stream while the layer itself runs.
