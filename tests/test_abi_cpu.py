@@ -139,3 +139,39 @@ def test_scaler_calls_validate_on_the_host(lib):
         with pytest.raises(B.MoeError) as ei:
             call()
         assert ei.value.code == code
+
+
+def test_expert_parallel_shares_partition_the_rows():
+    """Host logic of the expert-parallel latency model (Section 4.3): under the static placement
+    and under the oracle's Algorithm 1 + 2 outputs every permuted row belongs to exactly one rank,
+    a rank's local offsets cover its rows expert by expert, and replicas of one expert on one rank
+    merge in row order."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import placer_oracle as pl
+    from oracle import scaler_oracle as sc
+    from paper_2603_06350_amd import ep_sim
+
+    E, G = 16, 4
+    counts = si.zipf_loads(E, 5000, 1.2, seed=3).astype(np.int64)
+    counts[5] = 0
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    A = int(offsets[-1])
+    static = ep_sim.static_shares(offsets, E, G)
+    ep_sim.check_partition(static, A)
+    assert [int(s[1].size) for s in static] == [int(counts[g * 4:(g + 1) * 4].sum()) for g in range(G)]
+
+    replicas, _ = sc.expert_scaling(counts, 1, E, 0.2)
+    seg_offsets, seg_expert = sc.replica_segments(offsets, replicas)
+    gpu_of = pl.expert_placement(counts, replicas, G)[0]
+    S = int(np.sum(replicas))
+    placed = ep_sim.placed_shares(seg_offsets, seg_expert, np.asarray(gpu_of), S, G)
+    ep_sim.check_partition(placed, A)
+    for hosted, rows, local in placed:
+        assert np.all(np.diff(hosted) > 0) and local.size == hosted.size + 1
+        for i, e in enumerate(hosted):
+            mine = rows[local[i]:local[i + 1]]
+            assert np.all(np.diff(mine) > 0)                      # row order kept
+            assert mine.size == 0 or (mine[0] >= offsets[e] and mine[-1] < offsets[e + 1])
+    # the point of scaling + placement: the most loaded rank holds fewer rows
+    assert max(r.size for _, r, _ in placed) < max(r.size for _, r, _ in static)
