@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--predictor-accuracy", action="store_true",
                     help="also report how the loads predicted from x match those the same gate gives "
                          "on x + eps * noise (a residual-stream stand-in), for several eps")
+    ap.add_argument("--ffn-split", action="store_true",
+                    help="give the grouped FFN the workspace that lets it cut the tiles of an under-filled "
+                         "last round along K (moe_grouped_ffn_ws)")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -105,7 +108,8 @@ def main():
     L = si.make_layer(cfg)
     x, wg, w1, w3, w2 = (layer.to_device(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2"))
     bias = layer.to_device(L["gate_bias"])
-    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm,
+                           split_tiles=args.ffn_split)
     st = torch.cuda.current_stream()
     sh = buf.shape
 
@@ -117,7 +121,11 @@ def main():
                                 buf.ws_bytes, st)
 
     def call_ffn(part=None):
-        if fused and part is None:
+        if args.ffn_split:
+            B.moe_grouped_ffn_ws(sh, x if fused else buf.x_perm, buf.src_assign if fused else None,
+                                 buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 3 if part is None else part,
+                                 buf.ffn_ws, buf.ffn_ws_bytes, st)
+        elif fused and part is None:
             B.moe_grouped_ffn_gather(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
         elif fused:
             B.moe_grouped_ffn_gather_part(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h,
@@ -278,7 +286,8 @@ def main():
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
                                f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward",
                    "ffn_input": "x through the permutation map (moe_grouped_ffn_gather)" if fused
-                   else "materialised x_perm (moe_grouped_ffn)"},
+                   else "materialised x_perm (moe_grouped_ffn)",
+                   "ffn_split_tiles": bool(args.ffn_split)},
         "ffn_pct_of_bf16_mfma_peak": 100.0 * others["ffn_total_frac_of_mfma_peak"],
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
         "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,

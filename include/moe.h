@@ -160,6 +160,30 @@ int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x, const i
                                 const void* w2, void* h, void* y_perm, int part, void* hip_stream);
 
 /*
+ * moe_grouped_ffn / moe_grouped_ffn_gather (Section 3.2) with a workspace that lets the bf16 MFMA
+ * kernels cut tiles along the reduction dimension.  A GEMM's tiles run in rounds of the chip's
+ * compute units; when the last round is at most half full, each of its tiles is computed as 2 to
+ * 4 parts on otherwise idle units, the parts leave their fp32 accumulators in the workspace, and
+ * a small launch right after the GEMM adds them in part order (deterministic), rounds and stores
+ * once.  For such tiles the fp32 sum is grouped differently than in the calls without a
+ * workspace, so h and y_perm may differ from theirs in the last bit; all other rows are
+ * bit-identical.  Each GEMM costs one more (mostly empty) launch.
+ *   x, src_assign   src_assign == NULL: x is x_perm [T*k, d] as for moe_grouped_ffn;
+ *                   otherwise x [T, d] and the map, as for moe_grouped_ffn_gather
+ *   parts           1 = up-projection only, 2 = down-projection only, 3 = both
+ *   workspace       device memory, 16-byte aligned, at least moe_ffn_workspace_bytes() bytes
+ *                   (64 MiB on a 256-CU device), contents irrelevant; or NULL (then exactly
+ *                   moe_grouped_ffn / moe_grouped_ffn_gather).  Calls that share a workspace
+ *                   must not overlap in time.
+ * Errors as moe_grouped_ffn; MOE_ERR_WORKSPACE if workspace_bytes is too small.
+ */
+int moe_ffn_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes);
+int moe_grouped_ffn_ws(const moe_shape_t* shape, const void* x, const int32_t* src_assign,
+                       const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                       void* h, void* y_perm, int parts, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
+/*
  * Weighted combine (Section 2.2: the gather that collects and reorders expert
  * outputs):   y[t,:] = sum_{j<k} topk_w[t,j] * y_perm[dst_row[t*k+j], :]
  * summed in fp32 in ascending j, stored once in `dtype`.  y [T,d].

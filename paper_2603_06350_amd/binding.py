@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_route_ws", "moe_count_and_permute", "moe_grouped_ffn",
            "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
-           "moe_grouped_ffn_gather_part", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
+           "moe_grouped_ffn_gather_part", "moe_ffn_workspace_bytes", "moe_grouped_ffn_ws", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
            "moe_place_replicas",
            "moe_strerror")
 MOE_MAX_EXTRA_REPLICAS = 65536
@@ -61,6 +61,9 @@ def load():
     lib.moe_grouped_ffn_gather.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp]
     lib.moe_grouped_ffn_gather_part.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp,
                                                 ctypes.c_int, vp]
+    lib.moe_ffn_workspace_bytes.argtypes = [shp, ctypes.POINTER(ctypes.c_size_t)]
+    lib.moe_grouped_ffn_ws.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp,
+                                       ctypes.c_size_t, vp]
     lib.moe_combine.argtypes = [shp, vp, i32p, f32p, vp, vp]
     lib.moe_scale_replicas.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int64,
                                        ctypes.c_double, i32p, vp, vp]
@@ -161,6 +164,21 @@ def moe_grouped_ffn_gather_part(shape, x, src_assign, offsets, w1, w3, w2, h, y_
            load().moe_grouped_ffn_gather_part(ctypes.byref(shape), _ptr(x), _ptr(src_assign),
                                               _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(h),
                                               _ptr(y_perm), int(part), _stream(stream)))
+
+
+def moe_ffn_workspace_bytes(shape: MoeShape) -> int:
+    out = ctypes.c_size_t(0)
+    _check("moe_ffn_workspace_bytes",
+           load().moe_ffn_workspace_bytes(ctypes.byref(shape), ctypes.byref(out)))
+    return int(out.value)
+
+
+def moe_grouped_ffn_ws(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, parts, workspace,
+                       workspace_bytes, stream=None):
+    _check("moe_grouped_ffn_ws",
+           load().moe_grouped_ffn_ws(ctypes.byref(shape), _ptr(x), _ptr(src_assign), _ptr(offsets),
+                                     _ptr(w1), _ptr(w3), _ptr(w2), _ptr(h), _ptr(y_perm), int(parts),
+                                     _ptr(workspace), int(workspace_bytes), _stream(stream)))
 
 
 def moe_combine(shape, y_perm, dst_row, topk_w, y, stream=None):

@@ -50,6 +50,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
 enum TileMode { TILES_ALL = 0, TILES_MAIN = 1, TILES_SMALL = 2 };
+constexpr int BK_ELEMS = 64;    // K elements per stage of the MFMA kernels
 constexpr int SMALL_ROWS = 64;  // remainders up to this many rows go to the small-tile kernel
 
 struct GemmArgs {
@@ -72,7 +73,16 @@ struct GemmArgs {
   // n-tiles and K stages of the up- and the down-projection of the call this GEMM belongs to:
   // both take the main/small decision on the same sum, so they take the same one
   int pair_n_tiles[2], pair_kt[2];
+  // Split tiles (kernels built with SPLIT only): fp32 partial tiles, one slot per compute unit.
+  // nullptr: no tile is split.  split_phase 0: the GEMM itself; 1: the launch after it that adds
+  // up the parts of every split tile and stores it.
+  float* split_ws;
+  int split_phase;
 };
+
+constexpr int SPLIT_SLOT_FLOATS = 256 * 256;   // one partial tile (the largest: 256 x 256 fp32)
+constexpr int SPLIT_MAX_PARTS = 4;
+constexpr int SPLIT_MIN_STAGES = 8;            // K stages a part must keep
 
 // Row of `a` that holds GEMM row r.
 __device__ __forceinline__ int a_row_of(const GemmArgs& p, int r) {
@@ -83,6 +93,9 @@ __device__ __forceinline__ int a_row_of(const GemmArgs& p, int r) {
 
 struct TileCoord {
   int e, m_begin, m_end, n_tile;
+  // K split of a tile of the last, partial round (nparts == 1: the whole K range)
+  int part, nparts;
+  int pslot;   // partial-tile slot of this part; the parts of a tile have consecutive slots
 };
 
 // Maps a work-group to (expert, row range, n-tile).  Every wave computes this on its
@@ -113,6 +126,7 @@ __device__ __forceinline__ int wave_scan_add(int x) {
   return x;
 }
 
+template <bool SPLIT = false>
 __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int32_t* __restrict__ offsets = p.offsets;
   const int E = p.E, n_tiles = p.n_tiles, bm = p.bm_main, mode = p.mode;
@@ -144,6 +158,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   // list is a combination of the two
   const int incl_all = wave_scan_add(n_all), incl_small = wave_scan_add(n_small);
   bool fold = false;                             // small remainders ride in the main launch
+  int small_beside = 0;                          // ... or run as small tiles beside this main launch
   if (mode != TILES_ALL) {
     n_all = __builtin_amdgcn_readlane(incl_all, MOE_WAVE - 1);
     n_small = __builtin_amdgcn_readlane(incl_small, MOE_WAVE - 1);
@@ -162,6 +177,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
                     (static_cast<int64_t>(rounds_main) * cu * 10 + static_cast<int64_t>(tiles_small) * 6);
     }
     fold = cost_fold <= cost_split;
+    small_beside = __builtin_amdgcn_readfirstlane((mode == TILES_MAIN && !fold && n_small > 0) ? 1 : 0);
   }
   int local = 0;
 #pragma unroll
@@ -179,8 +195,42 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int per_xcd = (total + 7) / 8;
   const int xcd = blockIdx.x & 7;
   const int slot = blockIdx.x >> 3;
-  const int vid = xcd * per_xcd + slot;
-  if (slot >= per_xcd || vid >= total) return false;
+  int vid = xcd * per_xcd + slot;
+  tc.part = 0;
+  tc.nparts = 1;
+  tc.pslot = 0;
+  if (SPLIT && p.split_ws) {
+    // The tiles of an XCD's range run in rounds of its compute units.  If the last round is at
+    // most half full, its tiles are cut along K into as many parts as fit the idle units (every
+    // block of both launches takes the same decision from the same numbers); the grid of the GEMM
+    // has a round of extra blocks for the parts.
+    const int cus_x = max(1, (p.n_cu > 0 ? p.n_cu : 256) / 8);
+    const int full_x = per_xcd / cus_x * cus_x;
+    const int tail_x = per_xcd - full_x;
+    int parts = 1;
+    if (tail_x > 0 && 2 * tail_x <= cus_x)
+      parts = min(min(cus_x / tail_x, SPLIT_MAX_PARTS), (p.K / BK_ELEMS) / SPLIT_MIN_STAGES);
+    // small tiles in a launch of their own beside this one take the idle units already
+    if (parts < 2 || small_beside) parts = 1;
+    if (p.split_phase == 1) {
+      // the summing launch: block (xcd, t) takes split tile t of the XCD's last round
+      if (parts == 1 || slot >= tail_x) return false;
+      vid = xcd * per_xcd + full_x + slot;
+      tc.nparts = parts;
+      tc.pslot = xcd * cus_x + slot * parts;
+    } else if (slot >= full_x) {
+      const int j = slot - full_x;
+      const int t_local = j / parts;
+      if (t_local >= tail_x) return false;
+      vid = xcd * per_xcd + full_x + t_local;
+      tc.part = j - t_local * parts;
+      tc.nparts = parts;
+      tc.pslot = xcd * cus_x + j;                // j < tail_x * parts <= cus_x
+    }
+    if (vid >= total) return false;
+  } else if (slot >= per_xcd || vid >= total) {
+    return false;
+  }
   int run = incl - local;
   int found_e = -1, found_local = 0, found_mt = 1, found_ob = 0, found_oe = 0;
 #pragma unroll
@@ -227,7 +277,7 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
 // bf16 MFMA kernel
 // --------------------------------------------------------------------------------------------
 constexpr int BROWS = 256;      // weight rows per block tile
-constexpr int BK = 64;          // K elements per stage
+constexpr int BK = BK_ELEMS;    // K elements per stage
 constexpr int ROWB = BK * 2;    // bytes per tile row in LDS (eight 16-byte chunks)
 
 // Chunk swizzle of a 128-byte tile row: XOR with the row so that 16 consecutive rows x one
@@ -253,10 +303,75 @@ constexpr int ffn_lds_bytes(int bm, int nstage) {
   return ffn_half_ring(bm, nstage) ? 5 * bm * ROWB : nstage * (bm + BROWS) * ROWB;
 }
 
+// Epilogue of the MFMA kernels.  Accumulator (v, lane) holds out[row = m-sub-tile + lane%16]
+// [col = n-sub-tile + 4*(lane/16) + v]: 8-byte pieces scattered over 16 rows.  Each wave turns its
+// 16-row sub-tile around in a private LDS region (row pitch = row bytes + 32: the 32-byte runs
+// that the four lanes of a row write land in 8 banks, and 8 consecutive rows cover all 64) and
+// stores whole rows, 16 bytes per lane, so the L2 sees full-line writes.  Starts with a barrier:
+// every wave must be done with whatever else the block kept in LDS.
+template <int BM, bool GATED, int WM, int WN, int NSTAGE>
+__device__ __forceinline__ void ffn_store_tile(
+    const f32x4_t (&acc)[BROWS / WN / 16][BM / WM / 16], const TileCoord& tc, const GemmArgs& p,
+    unsigned char* lds, int wave, int lane, int mi_valid) {
+  constexpr int NW = WM * WN;
+  constexpr int MI = BM / WM / 16;
+  constexpr int NI = BROWS / WN / 16;
+  constexpr int NIH = GATED ? NI / 2 : NI;
+  constexpr int BN_OUT = GATED ? 128 : 256;
+  const int wm = wave / WN, wn = wave % WN;
+  const int l16 = lane & 15;
+  const int N = p.N;
+  const int n0 = tc.n_tile * BN_OUT;
+  __builtin_amdgcn_s_barrier();                   // every wave is done with the K-loop stages
+  asm volatile("" ::: "memory");
+  constexpr int CW = NIH * 16;                    // output columns of this wave
+  constexpr int PITCH = CW * 2 + 32;              // bytes
+  constexpr int LPR = CW * 2 / 16;                // lanes that store one row
+  constexpr int RPI = 64 / LPR;                   // rows per store instruction
+  static_assert(16 % RPI == 0 && NW * 16 * PITCH <= ffn_lds_bytes(BM, NSTAGE), "epilogue staging");
+  unsigned char* region = lds + wave * (16 * PITCH);
+  bf16_t* out = static_cast<bf16_t*>(p.out);
+  const int col0 = n0 + wn * CW;                  // first output column of this wave
+#pragma unroll
+  for (int mi = 0; mi < MI; ++mi) {
+    if (mi < mi_valid) {                          // wave-uniform
+#pragma unroll
+      for (int ni = 0; ni < NIH; ++ni) {
+        float o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (GATED)
+            o[u] = silu_mul(acc[ni][mi][u], acc[GATED ? ni + NIH : ni][mi][u]);
+          else
+            o[u] = acc[ni][mi][u];
+        }
+        const int c = ni * 16 + 4 * (lane >> 4);
+        *reinterpret_cast<uint2*>(region + l16 * PITCH + c * 2) =
+            make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
+      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 16;
+#pragma unroll
+      for (int it = 0; it < 16 / RPI; ++it) {
+        const int r = it * RPI + lane / LPR;
+        const int c = (lane % LPR) * 8;           // first column of this lane's 16 bytes
+        const uint4 v = *reinterpret_cast<const uint4*>(region + r * PITCH + c * 2);
+        const int gr = row_base + r;
+        if (gr < tc.m_end && col0 + c < N)
+          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) = v;
+      }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the region is reused
+    }
+  }
+}
+
 // BM x 256 block tile, WM x WN waves, NSTAGE LDS stages of 64 K-elements.
 // NSTAGE == 2: hand-ordered pipeline (large tiles, MFMA/L2 bound).
 // NSTAGE  > 2: ring with NSTAGE-1 stages of loads in flight (small tiles, latency bound).
-template <int BM, bool GATED, int WM, int WN, int NSTAGE>
+// SPLIT: tiles of the last, partial round may be cut along K (see decode_tile): a part leaves its
+// fp32 accumulators in the workspace instead of storing the tile, and ffn_sum_parts_kernel, the
+// next launch on the stream, adds the parts in part order and runs the epilogue.
+template <int BM, bool GATED, int WM, int WN, int NSTAGE, bool SPLIT = false>
 __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   constexpr int NW = WM * WN;                     // waves per block
   constexpr int KSTEPS = BK / 32;                 // MFMA k-steps per stage
@@ -274,13 +389,18 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   extern __shared__ __align__(1024) unsigned char lds[];
 
   TileCoord tc;
-  if (!decode_tile(p, tc)) return;
+  if (!decode_tile<SPLIT>(p, tc)) return;
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   const int wm = wave / WN, wn = wave % WN;
   const int K = p.K, N = p.N;
-  const int KT = K / BK;
+  int kt_first = 0, kt_count = K / BK;            // this block's K stages
+  if (SPLIT && tc.nparts > 1) {
+    kt_first = tc.part * kt_count / tc.nparts;
+    kt_count = (tc.part + 1) * kt_count / tc.nparts - kt_first;
+  }
+  const int KT = kt_count;
   const int n0 = tc.n_tile * BN_OUT;
   const bf16_t* A = static_cast<const bf16_t*>(p.a);
   const bf16_t* B0 = static_cast<const bf16_t*>(p.b0) + static_cast<int64_t>(tc.e) * N * K;
@@ -295,12 +415,14 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
   //      so each instruction has a uniform 64-bit base and a 32-bit per-lane offset.  Rows past
   //      the end of the segment (or of the weight matrix) re-read the last valid row.
   const bool gathered = p.src_assign != nullptr;  // uniform
+  const int k_first = kt_first * BK;              // first K element of this block
   const unsigned char* base_a = reinterpret_cast<const unsigned char*>(
-      gathered ? A : A + static_cast<int64_t>(tc.m_begin) * K);
+      (gathered ? A : A + static_cast<int64_t>(tc.m_begin) * K) + k_first);
   const unsigned char* base_b0 =
-      reinterpret_cast<const unsigned char*>(B0 + static_cast<int64_t>(n0) * K);
+      reinterpret_cast<const unsigned char*>(B0 + static_cast<int64_t>(n0) * K + k_first);
   const unsigned char* base_b1 =
-      GATED ? reinterpret_cast<const unsigned char*>(B1 + static_cast<int64_t>(n0) * K) : nullptr;
+      GATED ? reinterpret_cast<const unsigned char*>(B1 + static_cast<int64_t>(n0) * K + k_first)
+            : nullptr;
   uint32_t soff[NLOAD];
 #pragma unroll
   for (int i = 0; i < NLOAD; ++i) {
@@ -581,53 +703,58 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
 #undef MOE_W_OFF
   }
 
-  // ---- epilogue.  Accumulator (v, lane) holds out[row = m-sub-tile + lane%16]
-  //      [col = n-sub-tile + 4*(lane/16) + v]: 8-byte pieces scattered over 16 rows.
-  //      Each wave turns its 16-row sub-tile around in a private LDS region (row pitch = row
-  //      bytes + 32: the 32-byte runs that the four lanes of a row write land in 8 banks, and 8
-  //      consecutive rows cover all 64) and stores whole rows, 16 bytes per lane, so the L2 sees
-  //      full-line writes.
-  __builtin_amdgcn_s_barrier();                   // every wave is done with the K-loop stages
-  asm volatile("" ::: "memory");
-  constexpr int CW = NIH * 16;                    // output columns of this wave
-  constexpr int PITCH = CW * 2 + 32;              // bytes
-  constexpr int LPR = CW * 2 / 16;                // lanes that store one row
-  constexpr int RPI = 64 / LPR;                   // rows per store instruction
-  static_assert(16 % RPI == 0 && NW * 16 * PITCH <= ffn_lds_bytes(BM, NSTAGE), "epilogue staging");
-  unsigned char* region = lds + wave * (16 * PITCH);
-  bf16_t* out = static_cast<bf16_t*>(p.out);
-  const int col0 = n0 + wn * CW;                  // first output column of this wave
+  if (SPLIT && tc.nparts > 1) {
+    // a part of a split tile: the accumulators go to its slot, thread-major so that a thread's
+    // 16 bytes sit next to its neighbours'
+    constexpr int NT = NW * MOE_WAVE;
+    float* mine = p.split_ws + static_cast<int64_t>(tc.pslot) * SPLIT_SLOT_FLOATS;
 #pragma unroll
-  for (int mi = 0; mi < MI; ++mi) {
-    if (mi < mi_valid) {                          // wave-uniform
+    for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
-      for (int ni = 0; ni < NIH; ++ni) {
-        float o[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (GATED)
-            o[u] = silu_mul(acc[ni][mi][u], acc[GATED ? ni + NIH : ni][mi][u]);
-          else
-            o[u] = acc[ni][mi][u];
-        }
-        const int c = ni * 16 + 4 * (lane >> 4);
-        *reinterpret_cast<uint2*>(region + l16 * PITCH + c * 2) =
-            make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
-      }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
-      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 16;
-#pragma unroll
-      for (int it = 0; it < 16 / RPI; ++it) {
-        const int r = it * RPI + lane / LPR;
-        const int c = (lane % LPR) * 8;           // first column of this lane's 16 bytes
-        const uint4 v = *reinterpret_cast<const uint4*>(region + r * PITCH + c * 2);
-        const int gr = row_base + r;
-        if (gr < tc.m_end && col0 + c < N)
-          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) = v;
-      }
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the region is reused
-    }
+      for (int mi = 0; mi < MI; ++mi)
+        *reinterpret_cast<f32x4_t*>(mine + ((ni * MI + mi) * NT + static_cast<int>(threadIdx.x)) * 4) =
+            acc[ni][mi];
+    return;
   }
+  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid);
+}
+
+// The launch after a GEMM whose tiles may have been split: block (xcd, t) adds the parts of split
+// tile t of the XCD's last round in part order (so the sum does not depend on scheduling) and
+// stores the tile.  Finds nothing to do when no tile was split.
+template <int BM, bool GATED, int WM, int WN, int NSTAGE>
+__global__ __launch_bounds__(WM * WN * 64) void ffn_sum_parts_kernel(GemmArgs p) {
+  constexpr int NW = WM * WN;
+  constexpr int MI = BM / WM / 16;
+  constexpr int NI = BROWS / WN / 16;
+  constexpr int NT = NW * MOE_WAVE;
+  extern __shared__ __align__(1024) unsigned char lds[];
+  TileCoord tc;
+  if (!decode_tile<true>(p, tc)) return;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
+  const int wm = wave / WN;
+  const int rows_valid = min(tc.m_end - tc.m_begin, BM);
+  const int mi_valid = max(0, min(MI, (rows_valid - wm * (BM / WM) + 15) / 16));
+  f32x4_t acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const float* first = p.split_ws + static_cast<int64_t>(tc.pslot) * SPLIT_SLOT_FLOATS;
+  for (int q = 0; q < tc.nparts; ++q) {
+    const float* src = first + static_cast<int64_t>(q) * SPLIT_SLOT_FLOATS;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(
+            src + ((ni * MI + mi) * NT + static_cast<int>(threadIdx.x)) * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[ni][mi][u] += v[u];
+      }
+  }
+  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -735,22 +862,53 @@ static int64_t max_m_tiles(int64_t A, int E, int bm, int mode) {
   return A / bm + e_cap;   // TILES_MAIN may take every remainder: the same bound as TILES_ALL
 }
 
-template <int BM, bool GATED, int WM, int WN, int NSTAGE>
-static int launch_mfma(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t st) {
+template <int BM, bool GATED, int WM, int WN, int NSTAGE, bool SPLIT>
+static int launch_mfma_as(GemmArgs a, int mode, int bm_main, int64_t A, hipStream_t st) {
   constexpr int lds_bytes = ffn_lds_bytes(BM, NSTAGE);
   static LdsOnce once;
-  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>),
+  if (ensure_dynamic_lds(once,
+                         reinterpret_cast<const void*>(ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE, SPLIT>),
                          lds_bytes) != MOE_OK)
     return MOE_ERR_HIP;
   a.mode = mode;
   a.bm_main = bm_main;
+  a.split_phase = 0;
+  if (!SPLIT) a.split_ws = nullptr;
   int64_t grid = max_m_tiles(A, a.E, bm_main, mode) * a.n_tiles;
   if (grid == 0) return MOE_OK;       // no tile of this kind can exist
   grid = (grid + 7) / 8 * 8;
+  const int cu8 = (a.n_cu > 0 ? a.n_cu : 256) / 8 * 8;
+  if (SPLIT) grid += cu8;             // one more round of blocks for the parts of split tiles
   if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE>), dim3(static_cast<unsigned>(grid)),
-                     dim3(WM * WN * 64), lds_bytes, st, a);
-  return launch_status();
+  hipLaunchKernelGGL((ffn_mfma_kernel<BM, GATED, WM, WN, NSTAGE, SPLIT>),
+                     dim3(static_cast<unsigned>(grid)), dim3(WM * WN * 64), lds_bytes, st, a);
+  int rc = launch_status();
+  if (SPLIT && rc == MOE_OK) {
+    // the parts meet at the kernel boundary: one block per possible split tile
+    static LdsOnce once_sum;
+    if (ensure_dynamic_lds(once_sum,
+                           reinterpret_cast<const void*>(ffn_sum_parts_kernel<BM, GATED, WM, WN, NSTAGE>),
+                           lds_bytes) != MOE_OK)
+      return MOE_ERR_HIP;
+    a.split_phase = 1;
+    hipLaunchKernelGGL((ffn_sum_parts_kernel<BM, GATED, WM, WN, NSTAGE>), dim3(static_cast<unsigned>(cu8)),
+                       dim3(WM * WN * 64), lds_bytes, st, a);
+    rc = launch_status();
+  }
+  return rc;
+}
+
+// `split`: this launch may use the workspace for split tiles if the caller brought one.  Only
+// GEMMs with a long reduction do: a part must be worth the exchange (one 256 KiB store per part,
+// the summing launch), and a tile of fewer than 96 stages is too short for that (measured: the
+// up-projections of the four model shapes gain nothing, their down-projections up to 27 %).
+constexpr int SPLIT_MIN_K = 96 * BK_ELEMS;
+template <int BM, bool GATED, int WM, int WN, int NSTAGE>
+static int launch_mfma(const GemmArgs& a, int mode, int bm_main, int64_t A, hipStream_t st,
+                       bool split = false) {
+  return split && a.split_ws && a.K >= SPLIT_MIN_K
+             ? launch_mfma_as<BM, GATED, WM, WN, NSTAGE, true>(a, mode, bm_main, A, st)
+             : launch_mfma_as<BM, GATED, WM, WN, NSTAGE, false>(a, mode, bm_main, A, st);
 }
 
 template <typename T, bool GATED>
@@ -768,7 +926,7 @@ static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
 // Main tiles of one grouped GEMM on the MFMA path.
 template <bool GATED>
 static int mfma_gemm_main(const GemmArgs& g, int64_t A, hipStream_t st) {
-  return launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st);
+  return launch_mfma<256, GATED, 4, 2, 2>(g, TILES_MAIN, 256, A, st, true);
 }
 
 // The small remainders of the same GEMM.
@@ -815,8 +973,8 @@ static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, 
     // expert's weights once, which the latency-hiding ring of the 64-row tiles does best, and a
     // 256-row tile would be mostly padding.  One launch per GEMM.  (Measured at the Mixtral
     // shape: 64 rows per expert 0.85 -> 0.63 ms against 128-row main tiles plus remainders.)
-    if (up && (rc = launch_mfma<64, true, 2, 4, 4>(g1, TILES_ALL, 64, A, st)) != MOE_OK) return rc;
-    if (down) rc = launch_mfma<64, false, 2, 4, 4>(g2, TILES_ALL, 64, A, st);
+    if (up && (rc = launch_mfma<64, true, 2, 4, 4>(g1, TILES_ALL, 64, A, st, true)) != MOE_OK) return rc;
+    if (down) rc = launch_mfma<64, false, 2, 4, 4>(g2, TILES_ALL, 64, A, st, true);
     return rc;
   }
   std::lock_guard<std::mutex> lock(g_side_mutex);
@@ -838,7 +996,8 @@ static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, 
 // x_perm [T*k, d] with src_assign == nullptr, or x [T, d] with the src_assign map of the dispatch
 static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* src_assign,
                             const int32_t* offsets, const void* w1, const void* w3, const void* w2,
-                            void* h, void* y_perm, int parts, void* hip_stream) {
+                            void* h, void* y_perm, int parts, void* hip_stream,
+                            void* split_ws = nullptr) {
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
@@ -855,9 +1014,10 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   const int d = shape->d, F = shape->F, E = shape->E;
   const int n_cu = device_cu_count();
   GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_ALL, 64,
-              src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A), n_cu, {0, 0}, {0, 0}};
+              src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A), n_cu, {0, 0}, {0, 0},
+              static_cast<float*>(split_ws), 0};
   GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_ALL, 64,
-              nullptr, 1, static_cast<int>(A), n_cu, {0, 0}, {0, 0}};
+              nullptr, 1, static_cast<int>(A), n_cu, {0, 0}, {0, 0}, static_cast<float*>(split_ws), 0};
   const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
@@ -895,6 +1055,33 @@ extern "C" int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, con
                                void* hip_stream) {
   return moe::grouped_ffn_impl(shape, x_perm, nullptr, offsets, w1, w3, w2, h, y_perm, 3,
                                hip_stream);
+}
+
+// Bytes of the split-tile workspace on the current device: one fp32 partial tile per compute unit.
+static size_t ffn_split_workspace_bytes() {
+  const int n_cu = moe::device_cu_count();
+  return static_cast<size_t>(n_cu > 0 ? n_cu : 256) * moe::SPLIT_SLOT_FLOATS * sizeof(float);
+}
+
+extern "C" int moe_ffn_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes) {
+  if (!out_bytes) return MOE_ERR_INVALID_ARG;
+  const int rc = moe::check_shape(shape);
+  if (rc != MOE_OK) return rc;
+  *out_bytes = ffn_split_workspace_bytes();
+  return MOE_OK;
+}
+
+extern "C" int moe_grouped_ffn_ws(const moe_shape_t* shape, const void* x, const int32_t* src_assign,
+                                  const int32_t* offsets, const void* w1, const void* w3,
+                                  const void* w2, void* h, void* y_perm, int parts, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  if (parts < 1 || parts > 3) return MOE_ERR_INVALID_ARG;
+  if (workspace) {
+    if (!moe::aligned16(workspace)) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < ffn_split_workspace_bytes()) return MOE_ERR_WORKSPACE;
+  }
+  return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, parts,
+                               hip_stream, workspace);
 }
 
 extern "C" int moe_grouped_ffn_gather(const moe_shape_t* shape, const void* x,

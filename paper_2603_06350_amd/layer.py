@@ -29,7 +29,7 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 
 
 class MoeBuffers:
-    def __init__(self, T, d, E, k, F, dtype, renorm, device="cuda"):
+    def __init__(self, T, d, E, k, F, dtype, renorm, device="cuda", split_tiles=False):
         self.shape = B.make_shape(T, d, E, k, F, dtype, renorm)
         self.T, self.d, self.E, self.k, self.F = T, d, E, k, F
         tdt = torch.float32 if dtype == B.MOE_F32 else torch.bfloat16
@@ -48,6 +48,10 @@ class MoeBuffers:
         self.y = torch.empty((T, d), dtype=tdt, **kw)
         self.ws_bytes = B.moe_workspace_bytes(self.shape)
         self.workspace = torch.empty((self.ws_bytes,), dtype=torch.uint8, **kw)
+        # optional: the workspace that lets the grouped FFN cut the tiles of an under-filled last
+        # round along K (moe_grouped_ffn_ws)
+        self.ffn_ws_bytes = B.moe_ffn_workspace_bytes(self.shape) if split_tiles else 0
+        self.ffn_ws = torch.empty((self.ffn_ws_bytes,), dtype=torch.uint8, **kw) if split_tiles else None
 
     def forward(self, x, w_gate, w1, w3, w2, gate_bias=None, stream=None, export_scores=False,
                 gather_in_ffn=False):
@@ -60,7 +64,11 @@ class MoeBuffers:
         B.moe_count_and_permute(self.shape, x, self.topk_idx, self.counts, self.offsets,
                                 self.dst_row, self.src_assign, None if gather_in_ffn else self.x_perm,
                                 self.workspace, self.ws_bytes, s)
-        if gather_in_ffn:
+        if self.ffn_ws is not None:
+            B.moe_grouped_ffn_ws(self.shape, x if gather_in_ffn else self.x_perm,
+                                 self.src_assign if gather_in_ffn else None, self.offsets, w1, w3, w2,
+                                 self.h, self.y_perm, 3, self.ffn_ws, self.ffn_ws_bytes, s)
+        elif gather_in_ffn:
             B.moe_grouped_ffn_gather(self.shape, x, self.src_assign, self.offsets, w1, w3, w2,
                                      self.h, self.y_perm, s)
         else:

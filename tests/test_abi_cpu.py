@@ -141,6 +141,30 @@ def test_scaler_calls_validate_on_the_host(lib):
         assert ei.value.code == code
 
 
+def test_grouped_ffn_ws_validates_on_the_host(lib):
+    import synth_inputs as si
+    sh = B.make_shape(16, 64, 4, 2, 64, si.BF16, 1)
+    nb = B.moe_ffn_workspace_bytes(sh)
+    assert nb >= 256 * 256 * 4 and nb % (256 * 256 * 4) == 0      # one fp32 tile per compute unit
+    one = 0x1000   # never dereferenced: every case below fails validation first
+    args = (one, None, one, one, one, one, one, one)
+    cases = [
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 0, one, nb), -1),             # parts out of range
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 4, one, nb), -1),
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 3, one + 4, nb), -1),         # workspace misaligned
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 3, one, nb - 1), -3),         # workspace too small
+        (lambda: B.moe_grouped_ffn_ws(sh, None, None, one, one, one, one, one, one, 3, one, nb), -1),
+        (lambda: B.moe_grouped_ffn_ws(sh, one, None, None, one, one, one, one, one, 3, None, 0), -1),
+    ]
+    for call, code in cases:
+        with pytest.raises(B.MoeError) as ei:
+            call()
+        assert ei.value.code == code
+    # no tokens: nothing to do, with or without a workspace
+    empty = B.make_shape(0, 64, 4, 2, 64, si.BF16, 1)
+    B.moe_grouped_ffn_ws(empty, None, None, None, None, None, None, None, None, 3, None, 0)
+
+
 def test_expert_parallel_shares_partition_the_rows():
     """Host logic of the expert-parallel latency model (Section 4.3): under the static placement
     and under the oracle's Algorithm 1 + 2 outputs every permuted row belongs to exactly one rank,

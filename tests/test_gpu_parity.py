@@ -424,6 +424,64 @@ def test_grouped_ffn_every_stage_count_of_the_main_tile_ring(d, F):
     check_ffn(cfg, L, idx)
 
 
+SPLIT_CASES = [
+    # (shape, whether some tile must have been split); a GEMM is eligible from K = 6144 on
+    (dict(T=600, d=1024, E=2, k=1, F=6144), True),    # main tiles, down-projection cut in 4
+    (dict(T=64, d=1024, E=4, k=2, F=6144), True),     # 64-row tiles only (32 rows per expert)
+    (dict(T=600, d=6144, E=2, k=1, F=256), True),     # up-projection (gated) cut in 4
+    (dict(T=700, d=1024, E=2, k=1, F=6144, seed=11), None),   # remainders beside the main tiles
+    (dict(T=300, d=1024, E=2, k=1, F=2048), False),   # reductions too short: exactly the plain call
+]
+
+
+@pytest.mark.parametrize("case,expect_split", SPLIT_CASES,
+                         ids=lambda c: "T{T}_d{d}_E{E}_k{k}_F{F}".format(**c) if isinstance(c, dict) else "")
+@pytest.mark.parametrize("gathered", [False, True])
+def test_grouped_ffn_with_split_tiles(case, expect_split, gathered):
+    """moe_grouped_ffn_ws: tiles of an under-filled last round are computed in parts along K and
+    added up by the launch after the GEMM.  Oracle parity, run-to-run identical bits whatever the
+    workspace held before, rows within a bf16 step of the call without a workspace; where the
+    case says so, the split did happen (some bits differ) or cannot (identical bits)."""
+    cfg = si.small_config(**case)
+    L = si.make_layer(cfg)
+    idx, _, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm)
+    _, offsets = orc.expert_load(idx, cfg.E)
+    dst, src = orc.permutation(idx, cfg.E)
+    x_perm = orc.permute_rows(L["x"], dst, cfg.k)
+    ry, rh = orc.grouped_ffn(x_perm, offsets, L["w1"], L["w3"], L["w2"], return_h=True)
+    sh = shape_of(cfg)
+    A = cfg.T * cfg.k
+    nb = B.moe_ffn_workspace_bytes(sh)
+    d_x = dev(L["x"]) if gathered else dev(x_perm)
+    d_src = dev(src) if gathered else None
+    d_off, w1, w3, w2 = dev(offsets), dev(L["w1"]), dev(L["w3"]), dev(L["w2"])
+    outs = []
+    for fill in (0, 0x7F):                           # 0x7F7F7F7F is a large finite float: stale data would show
+        ws = torch.full((nb,), fill, dtype=torch.uint8, device="cuda")
+        h = torch.zeros((A, cfg.F), dtype=tdtype(cfg), device="cuda")
+        yp = torch.zeros((A, cfg.d), dtype=tdtype(cfg), device="cuda")
+        B.moe_grouped_ffn_ws(sh, d_x, d_src, d_off, w1, w3, w2, h, yp, 3, ws, nb)
+        torch.cuda.synchronize()
+        outs.append((h, yp))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    h, yp = outs[0]
+    tol = tol_of(cfg.dtype)
+    assert rel_err(orc.to_f64(host(h)), rh) <= tol
+    assert rel_err(orc.to_f64(host(yp)), ry) <= tol
+    # against the call without a workspace: the same rows up to the grouping of the fp32 sum
+    h0 = torch.zeros_like(h)
+    y0 = torch.zeros_like(yp)
+    B.moe_grouped_ffn_ws(sh, d_x, d_src, d_off, w1, w3, w2, h0, y0, 3, None, 0)
+    torch.cuda.synchronize()
+    assert (h.float() - h0.float()).abs().max().item() <= 2.0 ** -7 * h0.float().abs().max().item()
+    assert (yp.float() - y0.float()).abs().max().item() <= 2.0 ** -6 * y0.float().abs().max().item()
+    same = torch.equal(h, h0) and torch.equal(yp, y0)
+    if expect_split is True:
+        assert not same, "no tile was split"
+    elif expect_split is False:
+        assert same
+
+
 def test_grouped_ffn_skewed_and_empty_experts():
     cfg = si.small_config(T=700, d=128, E=8, k=2, F=256)
     L = si.make_layer(cfg)
