@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--predictor-accuracy", action="store_true",
                     help="also report how the loads predicted from x match those the same gate gives "
                          "on x + eps * noise (a residual-stream stand-in), for several eps")
+    ap.add_argument("--tokens", type=int, default=0, metavar="T",
+                    help="run the workload's layer on a batch of T tokens instead of its own size "
+                         "(same seeds and shapes otherwise; the JSON line names the batch)")
     ap.add_argument("--ffn-split", action="store_true",
                     help="give the grouped FFN the workspace that lets it cut the tiles of an under-filled "
                          "last round along K (moe_grouped_ffn_ws)")
@@ -105,6 +108,9 @@ def main():
         sys.exit(2)
     B.load()
     cfg = si.CONFIGS[args.workload]
+    if args.tokens > 0 and args.tokens != cfg.T:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name=f"{cfg.name}@T={args.tokens}", T=args.tokens)
     L = si.make_layer(cfg)
     x, wg, w1, w3, w2 = (layer.to_device(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2"))
     bias = layer.to_device(L["gate_bias"])
@@ -325,7 +331,7 @@ def main():
                                 buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
         out["ep_simulation"] = ep_sim.simulate(buf, x, w1, w3, w2, args.ep_sim)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, L, CPU_SAMPLE_TOKENS.get(cfg.name, min(cfg.T, 256)))
+        out["cpu_baseline"] = cpu_baseline(cfg, L, min(cfg.T, CPU_SAMPLE_TOKENS.get(cfg.name, 256)))
     print(json.dumps(out))
 
 

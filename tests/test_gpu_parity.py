@@ -305,9 +305,10 @@ DISPATCH_CASES = [
     dict(T=700, d=72, E=256, k=3),        # 128-thread variant, row not a multiple of 64 B
     dict(T=1, d=4096, E=8, k=2),
     dict(T=40, d=96, E=24, k=3, dtype=si.F32),
-    dict(T=512, d=64, E=16, k=2),         # 1024 assignments: the largest single-launch dispatch
-    dict(T=342, d=64, E=16, k=3),         # 1026: the smallest that takes the general path
-    dict(T=128, d=64, E=256, k=8),        # single launch, most experts
+    dict(T=128, d=64, E=16, k=2),         # 256 assignments: the largest single-launch dispatch
+    dict(T=512, d=64, E=16, k=2),         # 1024 assignments: two launches
+    dict(T=86, d=64, E=16, k=3),          # 258: the smallest that takes the general path
+    dict(T=32, d=64, E=256, k=8),         # single launch, most experts
 ]
 
 
@@ -331,7 +332,7 @@ def test_count_and_permute_degenerate_loads():
     cfg1 = si.small_config(T=600, d=64, E=16, k=1, F=64)
     check_dispatch(cfg1, L["x"], np.full((cfg.T, 1), 15, dtype=np.int32))
     # the same degenerate loads in a batch small enough for the single-launch dispatch
-    cfg2 = si.small_config(T=200, d=64, E=16, k=2, F=64)
+    cfg2 = si.small_config(T=120, d=64, E=16, k=2, F=64)
     L2 = si.make_layer(cfg2, parts=("x",))
     idx = np.zeros((cfg2.T, 2), dtype=np.int32)
     idx[:, 0], idx[:, 1] = 7, 3
