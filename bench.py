@@ -259,7 +259,8 @@ def main():
     tr = MEASURED_HBM_TRAFFIC.get(cfg.name)
     roofline = {"bound": "mfma",
                 "kernel": "ffn_mfma_kernel<gated>: part 1 of " +
-                          ("moe_grouped_ffn_gather" if fused else "moe_grouped_ffn") +
+                          ("moe_grouped_ffn_ws" if args.ffn_split else
+                           "moe_grouped_ffn_gather" if fused else "moe_grouped_ffn") +
                           ", main-tile launch plus the remainder launch that overlaps it on a side stream",
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
@@ -291,8 +292,9 @@ def main():
         "dtype": "bf16" if cfg.dtype == si.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
                                f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward",
-                   "ffn_input": "x through the permutation map (moe_grouped_ffn_gather)" if fused
-                   else "materialised x_perm (moe_grouped_ffn)",
+                   "ffn_input": ("x through the permutation map (%s)" % (
+                       "moe_grouped_ffn_ws" if args.ffn_split else "moe_grouped_ffn_gather")) if fused
+                   else "materialised x_perm (%s)" % ("moe_grouped_ffn_ws" if args.ffn_split else "moe_grouped_ffn"),
                    "ffn_split_tiles": bool(args.ffn_split)},
         "ffn_pct_of_bf16_mfma_peak": 100.0 * others["ffn_total_frac_of_mfma_peak"],
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
