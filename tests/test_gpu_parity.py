@@ -611,6 +611,43 @@ def test_layer_replays_from_a_hip_graph():
             assert np.array_equal(host(getattr(buf, n)), eager[n]), f"replay {rep}: {n} differs"
 
 
+def test_layer_with_split_tiles_replays_from_a_hip_graph():
+    """The layer with the split-tile workspace (the down-projection's tiles cut along K, summed by
+    the launch after the GEMM) captured into a HIP graph: every replay gives the eager bits, with
+    the workspace overwritten between the replays."""
+    cfg = si.small_config("bf16_graph_split", T=64, d=256, E=4, k=2, F=6144)
+    L = si.make_layer(cfg)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm, split_tiles=True)
+    plain = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    names = ("topk_idx", "counts", "dst_row", "h", "y_perm", "y")
+    buf.forward(*args)
+    plain.forward(*args)
+    torch.cuda.synchronize()
+    eager = {n: host(getattr(buf, n)).copy() for n in names}
+    ref = orc.moe_layer(L["x"], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm, None)
+    assert rel_err(orc.to_f64(eager["y"]), ref["y"]) <= tol_of(cfg.dtype)
+    assert not np.array_equal(eager["y_perm"], host(plain.y_perm)), "no tile was split"
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        buf.forward(*args)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=s):
+        buf.forward(*args)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for n in names:
+            getattr(buf, n).zero_()
+        buf.ffn_ws.fill_(0x7F)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            assert np.array_equal(host(getattr(buf, n)), eager[n]), f"replay {rep}: {n} differs"
+
+
 @pytest.mark.parametrize("cfg", LAYER_CASES, ids=lambda c: c.name)
 def test_ffn_reading_x_through_the_permutation_gives_the_same_bits(cfg):
     """moe_grouped_ffn_gather (no x_perm) against moe_grouped_ffn on the materialised x_perm."""
