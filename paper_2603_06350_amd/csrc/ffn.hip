@@ -23,6 +23,11 @@
 // The main tile keeps its operands in a ring of five 32 KiB half-stage slots (all of the CU's LDS):
 // two are being multiplied, up to three are in flight.
 //
+// moe_grouped_ffn_ws brings a workspace of fp32 partial tiles: a tile takes a whole compute unit,
+// so a GEMM runs in rounds of the chip, and when the last round of a GEMM with a long reduction
+// is at most half full its tiles are computed as 2 to 4 parts of the K range on the idle units
+// and added up, in part order, by a second small launch (ffn_sum_parts_kernel).
+//
 // bf16 kernels (gfx950): 512 threads = 8 waves, two per SIMD.  K step 64: both
 // operands are K-contiguous, so a tile row is 128 B = eight 16-byte chunks.  Tiles go
 // global -> LDS with 16-byte-per-lane buffer loads that write LDS directly (no register
