@@ -6,6 +6,13 @@ Routing, expert load and the permutation are compared with the full oracle on ev
 token (the oracle's routing is cheap at any size).  The expert FFN and the combine are
 compared on sampled tokens: for every sampled token the oracle computes the k expert
 outputs (h row, y_perm row) one by one from the same input bytes and combines them.
+On top of the random tokens, rows are chosen by where they sit in their expert's segment, because
+that is what decides which tile, which wave and which launch computes them at full size: the
+first and the last row of every segment, the two rows either side of every multiple of 16 rows
+inside it (every possible tile and sub-tile boundary, whatever the tile height), the whole tail
+of the segment past its last multiple of 256 rows (and at least its last 64 rows), and every row
+of the smallest non-empty and of the largest expert.  Each of those rows is compared (h and
+y_perm) on its own scale.
 The decode-shaped layer is small enough for the full oracle.
 """
 import numpy as np
@@ -102,6 +109,51 @@ def check_sampled_outputs(cfg, L, buf, ridx, rw, rd, n_tokens, seed=0):
     assert row_err.max() <= 4 * tol
 
 
+def structural_rows(offsets, E):
+    """Permuted rows picked by their position in the expert's segment (see the module text)."""
+    counts = np.diff(offsets)
+    nonempty = np.nonzero(counts > 0)[0]
+    whole = {int(nonempty[np.argmin(counts[nonempty])]), int(np.argmax(counts))}
+    rows, experts = [], []
+    for e in range(E):
+        lo, c = int(offsets[e]), int(counts[e])
+        if c == 0:
+            continue
+        if e in whole:
+            rel = np.arange(c)
+        else:
+            b = np.arange(16, c, 16)
+            tail = np.arange(min((c // 256) * 256, max(c - 64, 0)), c)
+            rel = np.unique(np.concatenate([[0, c - 1], b - 1, b, tail]))
+        rows.append(lo + rel)
+        experts.append(np.full(rel.size, e))
+    return np.concatenate(rows), np.concatenate(experts)
+
+
+def check_structural_rows(cfg, L, buf, ro, rs):
+    rows, experts = structural_rows(ro, cfg.E)
+    sel = torch.from_numpy(rows.astype(np.int64)).cuda()
+    h_gpu = orc.to_f64(layer.to_host(buf.h[sel]))
+    yp_gpu = orc.to_f64(layer.to_host(buf.y_perm[sel]))
+    toks = rs[rows] // cfg.k
+    tol = 1e-4 if cfg.dtype == si.F32 else 2e-2
+    worst = {"h": 0.0, "y_perm": 0.0}
+    scale = {"h": 0.0, "y_perm": 0.0}
+    for e in np.unique(experts):
+        m = experts == e
+        y_ref, h_ref = orc.expert_ffn(L["x"][toks[m]], L["w1"][e], L["w3"][e], L["w2"][e], return_h=True)
+        for name, g, r in (("h", h_gpu[m], h_ref), ("y_perm", yp_gpu[m], y_ref)):
+            row_err = np.abs(g - r).max(axis=1) / (np.abs(r).max(axis=1) + 1e-30)
+            bad = np.nonzero(row_err > 4 * tol)[0]
+            assert bad.size == 0, (f"{name}: expert {e}, segment row {rows[m][bad[0]] - ro[e]} of "
+                                   f"{ro[e + 1] - ro[e]}: rel err {row_err[bad[0]]:.3e} on the row's scale")
+            worst[name] = max(worst[name], float(np.abs(g - r).max()))
+            scale[name] = max(scale[name], float(np.abs(r).max()))
+    for name in worst:
+        assert worst[name] <= tol * scale[name], f"{name}: max rel err {worst[name] / scale[name]:.3e}"
+    return rows.size
+
+
 @pytest.mark.parametrize("name,n_tokens", [("mixtral", 40), ("finegrained", 48), ("skew", 48),
                                            ("skew_empty", 24), ("phi", 24), ("llama4", 16)])
 def test_full_size_sampled(name, n_tokens):
@@ -116,6 +168,9 @@ def test_full_size_sampled(name, n_tokens):
         assert (layer.to_host(buf.counts)[-4:] == 0).all()
     print("checking sampled expert outputs", flush=True)
     check_sampled_outputs(cfg, L, buf, ridx, rw, rd, n_tokens)
+    print("checking rows chosen by their place in the expert's segment", flush=True)
+    n = check_structural_rows(cfg, L, buf, ro, layer.to_host(buf.src_assign))
+    print(f"{n} of {cfg.A} permuted rows compared one by one", flush=True)
     # property that holds at any size: all of y is finite and no row was left unwritten
     y = buf.y.float()
     assert torch.isfinite(y).all() and (y.abs().amax(dim=1) > 0).all()

@@ -279,6 +279,48 @@ def test_degenerate_all_to_one_expert_and_single_token_and_k1():
     assert one["y"].shape == (1, cfg.d) and one["counts"].sum() == 2
 
 
+def test_topk_margin_hand_worked_and_scalar_sort():
+    """The margin is pinned by values worked out by hand and by a scalar sort per row: the gap
+    between the last chosen and the first rejected score, over the row's largest magnitude."""
+    score = np.array([[4.0, -8.0, 1.0, 3.0],      # sorted 4 3 1 -8, scale 8
+                      [0.5, 0.5, 0.25, -1.0],     # a tie at the top, scale 1
+                      [-2.0, -3.0, -5.0, -4.0],   # all negative: sorted -2 -3 -4 -5, scale 5
+                      [0.0, 0.0, 0.0, 0.0]],      # all-zero row: gap 0 (the scale floor avoids 0/0)
+                     dtype=np.float32)
+    assert orc.topk_margin(score, 1).tolist() == [1 / 8, 0.0, 1 / 5, 0.0]
+    assert orc.topk_margin(score, 2).tolist() == [2 / 8, 0.25, 1 / 5, 0.0]
+    assert orc.topk_margin(score, 3).tolist() == [9 / 8, 1.25, 1 / 5, 0.0]
+    assert np.all(np.isinf(orc.topk_margin(score, 4))) and np.all(orc.topk_margin(score, 4) > 0)
+    # scalar sort on random rows with repeated values, every k
+    rng = np.random.default_rng(11)
+    score = (rng.integers(-6, 7, size=(60, 7)) / 4).astype(np.float32)
+    for k in range(1, 7):
+        got = orc.topk_margin(score, k)
+        for t in range(score.shape[0]):
+            desc = sorted((float(v) for v in score[t]), reverse=True)
+            scale = max(max(abs(v) for v in desc), 1e-30)
+            assert got[t] == (desc[k - 1] - desc[k]) / scale
+    # the margin is the gap that separates what topk_select keeps from what it drops
+    for k in (1, 3, 6):
+        idx = orc.topk_select(score, k)
+        for t in range(score.shape[0]):
+            kept = score[t, idx[t]].astype(np.float64)
+            dropped = np.delete(score[t], idx[t]).astype(np.float64)
+            scale = max(np.abs(score[t]).max(), 1e-30)
+            assert orc.topk_margin(score, k)[t] == (kept.min() - dropped.max()) / scale
+
+    # planted slips: the gap one position early / late, or a scale taken from the signed maximum
+    def slipped(shift, signed_scale=False):
+        def f(score, k):
+            s = np.sort(score.astype(np.float64), axis=1)[:, ::-1]
+            scale = score.max(axis=1) if signed_scale else np.abs(score).max(axis=1)
+            return (s[:, k - 1 + shift] - s[:, k + shift]) / np.maximum(scale.astype(np.float64), 1e-30)
+        return f
+    hand = np.array([[4.0, -8.0, 1.0, 3.0]], dtype=np.float32)
+    assert slipped(-1)(hand, 2)[0] != 2 / 8 and slipped(1)(hand, 2)[0] != 2 / 8
+    assert slipped(0, True)(hand, 2)[0] != 2 / 8 and slipped(0)(hand, 2)[0] == 2 / 8
+
+
 def test_named_workloads_match_the_stored_margin_file(repo_root):
     import os
     rows = {}
@@ -287,6 +329,10 @@ def test_named_workloads_match_the_stored_margin_file(repo_root):
             if not line.startswith("#"):
                 p = line.split()
                 rows[p[0]] = p
+    # the file is regenerated whenever a workload is added: it lists every named one
+    assert set(rows) == set(si.CONFIGS)
+    for name, p in rows.items():
+        assert int(p[1]) == si.CONFIGS[name].seed
     for name in ("tiny", "decode", "mixtral"):
         cfg = si.CONFIGS[name]
         L = si.make_layer(cfg, parts=("x", "w_gate"))
