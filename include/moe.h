@@ -111,6 +111,25 @@ int moe_count_and_permute(const moe_shape_t* shape, const void* x, const int32_t
                           size_t workspace_bytes, void* hip_stream);
 
 /*
+ * moe_count_and_permute for callers that cannot allocate device memory or bring a workspace:
+ * code that runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same operation, same arguments (without the workspace) and the same results, bit for bit.  The
+ * block histograms that the other call keeps in the caller's workspace live in a fixed array of
+ * MOE_STATIC_SCRATCH_BYTES bytes inside the library's device image (one copy per GPU that the
+ * library runs on, held until the process ends).  The call allocates and frees nothing; the first
+ * call on a device looks up the array's address there (make that call outside a stream capture).
+ * Limit: ceil(T / 256) * E * 4 bytes must fit the array (blocks of 128 tokens instead of 256 when
+ * E > 128): up to 131072 tokens at E = 256, a million at E = 64; a larger batch returns
+ * MOE_ERR_WORKSPACE and enqueues nothing.  Nothing in the array has to start at zero (every entry is
+ * written before it is read), but all calls on one GPU share it: calls that overlap in time on
+ * one GPU (two streams, or two host threads) race; order them on one stream.
+ */
+#define MOE_STATIC_SCRATCH_BYTES (1u << 20)
+int moe_count_and_permute_static(const moe_shape_t* shape, const void* x, const int32_t* topk_idx,
+                                 int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                                 int32_t* src_assign, void* x_perm, void* hip_stream);
+
+/*
  * Grouped expert FFN (Section 3.2: expert computation dominates the layer).
  * For every expert e and every row r in [offsets[e], offsets[e+1]):
  *   h[r,:]      = silu(w1[e] x_perm[r]) * (w3[e] x_perm[r])     silu(z) = z / (1 + exp(-z))

@@ -17,12 +17,14 @@ _LIB_PATH = os.environ.get("MOE_GFX950_LIB") or os.path.join(
     os.path.dirname(os.path.abspath(__file__)), "libmoe_gfx950.so")
 _lib = None
 
-EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_route_ws", "moe_count_and_permute", "moe_grouped_ffn",
+EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_route_ws", "moe_count_and_permute",
+           "moe_count_and_permute_static", "moe_grouped_ffn",
            "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
            "moe_grouped_ffn_gather_part", "moe_ffn_workspace_bytes", "moe_grouped_ffn_ws", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
            "moe_place_replicas",
            "moe_strerror")
 MOE_MAX_EXTRA_REPLICAS = 65536
+MOE_STATIC_SCRATCH_BYTES = 1 << 20
 
 
 class MoeShape(ctypes.Structure):
@@ -56,6 +58,7 @@ def load():
     lib.moe_route_ws.argtypes = [shp, vp, vp, f32p, i32p, f32p, f32p, vp, ctypes.c_size_t, vp]
     lib.moe_count_and_permute.argtypes = [shp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp,
                                           ctypes.c_size_t, vp]
+    lib.moe_count_and_permute_static.argtypes = [shp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp]
     lib.moe_grouped_ffn.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, vp]
     lib.moe_grouped_ffn_part.argtypes = [shp, vp, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp]
     lib.moe_grouped_ffn_gather.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp]
@@ -136,6 +139,14 @@ def moe_count_and_permute(shape, x, topk_idx, counts, offsets, dst_row, src_assi
                                         _ptr(offsets), _ptr(dst_row), _ptr(src_assign),
                                         _ptr(x_perm), _ptr(workspace),
                                         ctypes.c_size_t(int(workspace_bytes)), _stream(stream)))
+
+
+def moe_count_and_permute_static(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm,
+                                 stream=None):
+    _check("moe_count_and_permute_static",
+           load().moe_count_and_permute_static(ctypes.byref(shape), _ptr(x), _ptr(topk_idx),
+                                               _ptr(counts), _ptr(offsets), _ptr(dst_row),
+                                               _ptr(src_assign), _ptr(x_perm), _stream(stream)))
 
 
 def moe_grouped_ffn(shape, x_perm, offsets, w1, w3, w2, h, y_perm, stream=None):

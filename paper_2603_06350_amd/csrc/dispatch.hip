@@ -17,6 +17,8 @@
 //   3. gather_kernel one wave per token: reads the token row once (16 B per
 //                    lane, coalesced), writes it to its k destination rows.
 //                    HBM-bound: T*d*b bytes read, T*k*d*b written.
+#include <mutex>
+
 #include "moe_internal.h"
 
 namespace moe {
@@ -297,56 +299,120 @@ extern "C" int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes) 
   return MOE_OK;
 }
 
+namespace moe {
+
+// Bytes of partial[blocks][E] that the two-launch dispatch keeps between hist_kernel and rank_kernel.
+static size_t dispatch_partial_bytes(const moe_shape_t* shape) {
+  const int nth = dispatch_threads(shape->E);
+  const int64_t nb = (static_cast<int64_t>(shape->T) + nth - 1) / nth;
+  return static_cast<size_t>(nb > 0 ? nb : 1) * shape->E * sizeof(int32_t);
+}
+
+// Everything after the checks of the workspace: `partial` holds dispatch_partial_bytes() bytes.
+// hist_kernel writes every entry of it that rank_kernel reads, so its old contents do not matter.
+static int count_and_permute_impl(const moe_shape_t* shape, const void* x, const int32_t* topk_idx,
+                                  int32_t* counts, int32_t* offsets, int32_t* dst_row,
+                                  int32_t* src_assign, void* x_perm, int32_t* partial,
+                                  hipStream_t st) {
+  const int T = shape->T, k = shape->k, E = shape->E;
+  const int nth = dispatch_threads(E);
+  const int nb = (T + nth - 1) / nth;
+  const size_t lds = static_cast<size_t>(E) * nth * 2 + static_cast<size_t>(E) * 8;
+  // T == 0 still defines counts = 0 and offsets = 0: one block with no tokens does that.
+  const int grid = nb > 0 ? nb : 1;
+  if (static_cast<int64_t>(T) * k <= RS_MAX_A) {
+    hipLaunchKernelGGL(rank_small_kernel, dim3(1), dim3(256), 0, st, topk_idx, T * k, E, counts,
+                       offsets, dst_row, src_assign);
+  } else if (nth == 256) {
+    static LdsOnce once;
+    if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(rank_kernel<256>),
+                           128 * 256 * 2 + 128 * 8) != MOE_OK)
+      return MOE_ERR_HIP;
+    hipLaunchKernelGGL(hist_kernel<256>, dim3(grid), dim3(256), 0, st, topk_idx, T, k, E, partial);
+    hipLaunchKernelGGL(rank_kernel<256>, dim3(grid), dim3(256), lds, st, topk_idx, T, k, E, partial,
+                       grid, counts, offsets, dst_row, src_assign);
+  } else {
+    static LdsOnce once;
+    if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(rank_kernel<128>),
+                           256 * 128 * 2 + 256 * 8) != MOE_OK)
+      return MOE_ERR_HIP;
+    hipLaunchKernelGGL(hist_kernel<128>, dim3(grid), dim3(128), 0, st, topk_idx, T, k, E, partial);
+    hipLaunchKernelGGL(rank_kernel<128>, dim3(grid), dim3(128), lds, st, topk_idx, T, k, E, partial,
+                       grid, counts, offsets, dst_row, src_assign);
+  }
+  if (T > 0 && x_perm) {
+    const int row16 = static_cast<int>(static_cast<int64_t>(shape->d) * elem_bytes(shape->dtype) / 16);
+    hipLaunchKernelGGL(gather_kernel, dim3((T + 3) / 4), dim3(256), 0, st,
+                       static_cast<const uint4*>(x), dst_row, static_cast<uint4*>(x_perm), T, k,
+                       row16, T * k);
+  }
+  return launch_status();
+}
+
+static int check_dispatch_args(const moe_shape_t* shape, const void* x, const int32_t* topk_idx,
+                               const int32_t* counts, const int32_t* offsets, const int32_t* dst_row,
+                               const int32_t* src_assign, const void* x_perm) {
+  const int rc = check_shape(shape);
+  if (rc != MOE_OK) return rc;
+  if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
+  if (shape->T > 0 && (!topk_idx || !dst_row || !src_assign)) return MOE_ERR_INVALID_ARG;
+  if (shape->T > 0 && x_perm && (!x || !aligned16(x) || !aligned16(x_perm))) return MOE_ERR_INVALID_ARG;
+  return MOE_OK;
+}
+
+// ---- the dispatch for callers that cannot allocate ------------------------------------------
+// The block histograms of moe_count_and_permute_static live in this array instead of a caller's
+// workspace: one copy per GPU, held for the life of the process.  In host code the array's name
+// is only a handle for the runtime: the address the kernels are given is looked up once per
+// device with hipGetSymbolAddress and kept.
+static __device__ __align__(256) unsigned char scratch[MOE_STATIC_SCRATCH_BYTES];
+static void* g_scratch_addr[MOE_MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MOE_MAX_DEVICES) return MOE_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_addr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return MOE_ERR_HIP;
+    }
+    g_scratch_addr[dev] = p;
+  }
+  *out = g_scratch_addr[dev];
+  return MOE_OK;
+}
+
+}  // namespace moe
+
 extern "C" int moe_count_and_permute(const moe_shape_t* shape, const void* x,
                                      const int32_t* topk_idx, int32_t* counts, int32_t* offsets,
                                      int32_t* dst_row, int32_t* src_assign, void* x_perm,
                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = moe::check_shape(shape);
+  const int rc = moe::check_dispatch_args(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm);
   if (rc != MOE_OK) return rc;
-  if (!counts || !offsets) return MOE_ERR_INVALID_ARG;
   size_t need = 0;
   moe_workspace_bytes(shape, &need);
   if (!workspace || !moe::aligned16(workspace)) return MOE_ERR_INVALID_ARG;
   if (workspace_bytes < need) return MOE_ERR_WORKSPACE;
-  const int T = shape->T, k = shape->k, E = shape->E;
-  if (T > 0 && (!topk_idx || !dst_row || !src_assign)) return MOE_ERR_INVALID_ARG;
-  if (T > 0 && x_perm && (!x || !moe::aligned16(x) || !moe::aligned16(x_perm)))
-    return MOE_ERR_INVALID_ARG;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  const int nth = moe::dispatch_threads(E);
-  const int nb = (T + nth - 1) / nth;
-  int32_t* partial = static_cast<int32_t*>(workspace);
-  const size_t lds = static_cast<size_t>(E) * nth * 2 + static_cast<size_t>(E) * 8;
-  // T == 0 still defines counts = 0 and offsets = 0: one block with no tokens does that.
-  const int grid = nb > 0 ? nb : 1;
-  if (static_cast<int64_t>(T) * k <= moe::RS_MAX_A) {
-    hipLaunchKernelGGL(moe::rank_small_kernel, dim3(1), dim3(256), 0, st, topk_idx, T * k, E, counts,
-                       offsets, dst_row, src_assign);
-  } else if (nth == 256) {
-    static moe::LdsOnce once;
-    if (moe::ensure_dynamic_lds(once, reinterpret_cast<const void*>(moe::rank_kernel<256>),
-                                128 * 256 * 2 + 128 * 8) != MOE_OK)
-      return MOE_ERR_HIP;
-    hipLaunchKernelGGL(moe::hist_kernel<256>, dim3(grid), dim3(256), 0, st, topk_idx, T, k, E,
-                       partial);
-    hipLaunchKernelGGL(moe::rank_kernel<256>, dim3(grid), dim3(256), lds, st, topk_idx, T, k, E,
-                       partial, grid, counts, offsets, dst_row, src_assign);
-  } else {
-    static moe::LdsOnce once;
-    if (moe::ensure_dynamic_lds(once, reinterpret_cast<const void*>(moe::rank_kernel<128>),
-                                256 * 128 * 2 + 256 * 8) != MOE_OK)
-      return MOE_ERR_HIP;
-    hipLaunchKernelGGL(moe::hist_kernel<128>, dim3(grid), dim3(128), 0, st, topk_idx, T, k, E,
-                       partial);
-    hipLaunchKernelGGL(moe::rank_kernel<128>, dim3(grid), dim3(128), lds, st, topk_idx, T, k, E,
-                       partial, grid, counts, offsets, dst_row, src_assign);
-  }
-  if (T > 0 && x_perm) {
-    const int row16 = static_cast<int>(static_cast<int64_t>(shape->d) *
-                                       moe::elem_bytes(shape->dtype) / 16);
-    hipLaunchKernelGGL(moe::gather_kernel, dim3((T + 3) / 4), dim3(256), 0, st,
-                       static_cast<const uint4*>(x), dst_row, static_cast<uint4*>(x_perm), T, k,
-                       row16, T * k);
-  }
-  return moe::launch_status();
+  return moe::count_and_permute_impl(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm,
+                                     static_cast<int32_t*>(workspace),
+                                     static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int moe_count_and_permute_static(const moe_shape_t* shape, const void* x,
+                                            const int32_t* topk_idx, int32_t* counts,
+                                            int32_t* offsets, int32_t* dst_row, int32_t* src_assign,
+                                            void* x_perm, void* hip_stream) {
+  const int rc = moe::check_dispatch_args(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm);
+  if (rc != MOE_OK) return rc;
+  // the batch must fit the fixed array: ceil(T / 256) * E * 4 bytes (blocks of 128 tokens above 128 experts)
+  if (moe::dispatch_partial_bytes(shape) > MOE_STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;
+  void* partial = nullptr;
+  if (moe::static_scratch(&partial) != MOE_OK) return MOE_ERR_HIP;
+  return moe::count_and_permute_impl(shape, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm,
+                                     static_cast<int32_t*>(partial),
+                                     static_cast<hipStream_t>(hip_stream));
 }
