@@ -25,16 +25,11 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
-# HBM bytes (read, written) of one launch of the dominant call, the gated up-projection GEMM (its
-# main-tile and remainder kernels together), from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`
-# runs of this script, each counter scaled by what it reads for the 1 GiB calibration copy below
-# (factors 2.000 and 1.000).  The summaries are under profiles/; a workload without one reports null.
-MEASURED_HBM_TRAFFIC = {
-    "mixtral": {"read_bytes": 2809.0e6 + 942.4e6, "written_bytes": 232.4e6 + 2.5e6,
-                "source": "profiles/mixtral_layer_all_kernels.md"},
-}
-
-CPU_SAMPLE_TOKENS = {"mixtral": 2048, "phi": 2048, "llama4": 2048, "finegrained": 2048, "skew": 2048, "decode": 32, "tiny": 64}
+# HBM-bound calls at a batch where bandwidth, not launch latency, decides: T tokens of the Mixtral
+# hidden size and routing fan-out (x is 512 MiB, x_perm and y_perm 1 GiB each, so every call
+# streams far more than the 256 MB last-level cache holds; two buffer sets alternate on top)
+HBM_BOUND_SHAPE = dict(T=65536, d=4096, E=8, k=2)
+HBM_BOUND_ITERS = 200
 
 
 def algorithmic_work(cfg):
@@ -46,6 +41,8 @@ def algorithmic_work(cfg):
         "permute_bytes": T * d * b + A * d * b + 4 * A + 8 * A + 8 * E,
         "permute_maps_only_bytes": 4 * A + 8 * A + 8 * E,
         "ffn_up_flops": 4 * d * F * A,        # two d x F products per routed row
+        # W1 and W3 of every expert once, the activation rows once, h written once
+        "ffn_up_bytes": 2 * E * d * F * b + A * d * b + A * F * b,
         "ffn_down_flops": 2 * d * F * A,
         "combine_bytes": A * d * b + T * d * b + 8 * A,
     }
@@ -63,9 +60,90 @@ def cpu_baseline(cfg, L, n_tokens):
     orc.moe_layer(L["x"][:n_tokens], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm,
                   L["gate_bias"])
     dt = time.perf_counter() - t0
+    which = "the whole batch" if n_tokens == cfg.T else f"first {n_tokens} of {cfg.T} tokens"
     return {"value": n_tokens / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {n_tokens} of {cfg.T} tokens through the full layer (all {cfg.E} "
+            "sample": f"{which} ({n_tokens} tokens) through the full layer (all {cfg.E} "
                       f"experts' weights, fp64), {dt:.1f} s wall"}
+
+
+def measured_hbm_traffic(cfg_name, entry_point):
+    """HBM bytes of one launch of the dominant call from the rocprofv3 --pmc summary under profiles/
+    (FETCH_SIZE and WRITE_SIZE runs of this script, each scaled by what the counter reads for the
+    1 GiB calibration copy).  The summary names the workload, the entry point and the SHA-256 of
+    csrc/ffn.hip it was taken with; a figure taken with another kernel source, another entry point
+    or another workload is not reported (None)."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"{cfg_name}_ffn_up_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    fields = dict(re.findall(r"^([a-z_0-9]+):\s*(\S+)\s*$", open(path).read(), flags=re.M))
+    src = os.path.join(ROOT, "paper_2603_06350_amd", "csrc", "ffn.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    if fields.get("ffn_hip_sha256") != sha or fields.get("entry_point") != entry_point or \
+            fields.get("workload") != cfg_name:
+        return None
+    return {"read_bytes": float(fields["hbm_read_bytes"]), "written_bytes": float(fields["hbm_written_bytes"]),
+            "source": os.path.relpath(path, ROOT)}
+
+
+def hbm_bound_calls(torch, si, B, layer, st):
+    """moe_route, moe_count_and_permute (with the row copy) and moe_combine at a bandwidth-bound
+    batch: average time of HBM_BOUND_ITERS launches each (HIP events on the launch stream), two
+    buffer sets alternating, algorithmic bytes / time against the HBM peak."""
+    T, d, E, k = (HBM_BOUND_SHAPE[n] for n in "TdEk")
+    cfg = si.small_config("hbm_bound", T=T, d=d, E=E, k=k, F=64, dtype=si.BF16, renorm=1, seed=8008)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    wg = layer.to_device(L["w_gate"])
+    sh = B.make_shape(T, d, E, k, 64, B.MOE_BF16, 1)
+    A = T * k
+    ws_bytes = B.moe_workspace_bytes(sh)
+    sets = []
+    for _ in range(2):
+        kw = dict(device="cuda")
+        sets.append(dict(
+            x=layer.to_device(L["x"]),
+            topk_idx=torch.empty((T, k), dtype=torch.int32, **kw),
+            topk_w=torch.empty((T, k), dtype=torch.float32, **kw),
+            counts=torch.empty((E,), dtype=torch.int32, **kw),
+            offsets=torch.empty((E + 1,), dtype=torch.int32, **kw),
+            dst_row=torch.empty((A,), dtype=torch.int32, **kw),
+            src_assign=torch.empty((A,), dtype=torch.int32, **kw),
+            x_perm=torch.empty((A, d), dtype=torch.bfloat16, **kw),
+            y=torch.empty((T, d), dtype=torch.bfloat16, **kw),
+            ws=torch.empty((ws_bytes,), dtype=torch.uint8, **kw)))
+    del L
+
+    def route(b):
+        B.moe_route_ws(sh, b["x"], wg, None, b["topk_idx"], b["topk_w"], None, b["ws"], ws_bytes, st)
+
+    def permute(b):
+        B.moe_count_and_permute(sh, b["x"], b["topk_idx"], b["counts"], b["offsets"], b["dst_row"],
+                                b["src_assign"], b["x_perm"], b["ws"], ws_bytes, st)
+
+    def combine(b):       # the permuted activations stand in for the expert outputs: same bytes moved
+        B.moe_combine(sh, b["x_perm"], b["dst_row"], b["topk_w"], b["y"], st)
+
+    b = 2  # bytes per element
+    work = {"route": T * d * b + E * d * b + 8 * A,
+            "count_and_permute": T * d * b + A * d * b + 4 * A + 8 * A + 8 * E,
+            "combine": A * d * b + T * d * b + 8 * A}
+    out = {"shape": f"T={T} d={d} E={E} k={k} bf16", "iterations": HBM_BOUND_ITERS,
+           "buffer_sets": len(sets), "hbm_peak_gbs": PEAK_HBM_GBS}
+    for name, fn in (("route", route), ("count_and_permute", permute), ("combine", combine)):
+        for bset in sets:
+            fn(bset)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(st)
+        for it in range(HBM_BOUND_ITERS):
+            fn(sets[it & 1])
+        e1.record(st)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / HBM_BOUND_ITERS * 1e3
+        gbs = work[name] / (us * 1e-6) / 1e9
+        out[name] = {"us": us, "algorithmic_bytes": work[name], "gbs": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+    return out
 
 
 def main():
@@ -90,6 +168,8 @@ def main():
     ap.add_argument("--ffn-split", action="store_true",
                     help="give the grouped FFN the workspace that lets it cut the tiles of an under-filled "
                          "last round along K (moe_grouped_ffn_ws)")
+    ap.add_argument("--no-hbm-bound", action="store_true",
+                    help="skip the timings of route / count+permute / combine at the bandwidth-bound batch")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -119,33 +199,73 @@ def main():
     st = torch.cuda.current_stream()
     sh = buf.shape
 
+    def ffn_entry(fused):
+        return ("moe_grouped_ffn_ws" if args.ffn_split else
+                "moe_grouped_ffn_gather" if fused else "moe_grouped_ffn")
+
+    def make_calls(fused):
+        def call_route():
+            B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
+
+        def call_permute():
+            B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
+                                    buf.src_assign, None if fused else buf.x_perm, buf.workspace,
+                                    buf.ws_bytes, st)
+
+        def call_ffn(part=None):
+            if args.ffn_split:
+                B.moe_grouped_ffn_ws(sh, x if fused else buf.x_perm, buf.src_assign if fused else None,
+                                     buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 3 if part is None else part,
+                                     buf.ffn_ws, buf.ffn_ws_bytes, st)
+            elif fused and part is None:
+                B.moe_grouped_ffn_gather(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+            elif fused:
+                B.moe_grouped_ffn_gather_part(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h,
+                                              buf.y_perm, part, st)
+            elif part is None:
+                B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
+            else:
+                B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, part, st)
+
+        def call_combine():
+            B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
+
+        return call_route, call_permute, call_ffn, call_combine
+
+    def time_form(fused, warmup, steps):
+        """ms per step of the whole path (wall clock around `steps` steps), and the average, minimum and
+        median duration of every call from HIP events recorded on the launch stream."""
+        call_route, call_permute, call_ffn, call_combine = make_calls(fused)
+        for _ in range(warmup):
+            call_route(), call_permute(), call_ffn(), call_combine()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            call_route(), call_permute(), call_ffn(), call_combine()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        # (torch events record on the current stream, which is the stream every call is given)
+        names = ["route", "count_and_permute", "ffn_up", "ffn_down", "combine"]
+        fns = [call_route, call_permute, lambda: call_ffn(1), lambda: call_ffn(2), call_combine]
+        n_ev = min(steps, 50)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(n_ev)]
+        for it in range(n_ev):
+            evs[it][0].record(st)
+            for i, fn in enumerate(fns):
+                fn()
+                evs[it][i + 1].record(st)
+        torch.cuda.synchronize()
+        samples = {n: sorted(evs[it][i].elapsed_time(evs[it][i + 1]) for it in range(n_ev))
+                   for i, n in enumerate(names)}
+        return ms, {"avg": {n: sum(v) / len(v) for n, v in samples.items()},
+                    "min": {n: v[0] for n, v in samples.items()},
+                    "median": {n: v[len(v) // 2] for n, v in samples.items()}}
+
     fused = not args.materialize_x_perm
 
-    def call_permute():
-        B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
-                                buf.src_assign, None if fused else buf.x_perm, buf.workspace,
-                                buf.ws_bytes, st)
-
-    def call_ffn(part=None):
-        if args.ffn_split:
-            B.moe_grouped_ffn_ws(sh, x if fused else buf.x_perm, buf.src_assign if fused else None,
-                                 buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 3 if part is None else part,
-                                 buf.ffn_ws, buf.ffn_ws_bytes, st)
-        elif fused and part is None:
-            B.moe_grouped_ffn_gather(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
-        elif fused:
-            B.moe_grouped_ffn_gather_part(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.h,
-                                          buf.y_perm, part, st)
-        elif part is None:
-            B.moe_grouped_ffn(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, st)
-        else:
-            B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, part, st)
-
     def step():
-        B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
-        call_permute()
-        call_ffn()
-        B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
+        for fn in make_calls(fused):
+            fn()
 
     # One plain copy kernel of known size (1 GiB read + 1 GiB written) so that a profiler's
     # HBM byte counters can be scaled against a known quantity.  Outside the timed region.
@@ -155,40 +275,15 @@ def main():
     torch.cuda.synchronize()
     del calib_src, calib_dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-
-    # Per-kernel durations with HIP events on the launch stream (torch events record on the
-    # current stream, which is the stream every call above is given).
-    names = ["route", "count_and_permute", "ffn_up", "ffn_down", "combine"]
-    n_ev = min(args.steps, 50)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(n_ev)]
-    for it in range(n_ev):
-        e = evs[it]
-        e[0].record(st)
-        B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
-        e[1].record(st)
-        call_permute()
-        e[2].record(st)
-        call_ffn(1)
-        e[3].record(st)
-        call_ffn(2)
-        e[4].record(st)
-        B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
-        e[5].record(st)
-    torch.cuda.synchronize()
-    samples = {n: sorted(evs[it][i].elapsed_time(evs[it][i + 1]) for it in range(n_ev))
-               for i, n in enumerate(names)}
-    per_call_ms = {n: sum(v) / len(v) for n, v in samples.items()}
-    per_call_ms_min = {n: v[0] for n, v in samples.items()}
-    per_call_ms_median = {n: v[len(v) // 2] for n, v in samples.items()}
+    ms_per_step, calls = time_form(fused, args.warmup, args.steps)
+    per_call_ms, per_call_ms_min, per_call_ms_median = calls["avg"], calls["min"], calls["median"]
+    # the boundary's four calls with a written x_perm (moe_grouped_ffn on it), timed the same way
+    four_call = None
+    if fused and not args.ffn_split:
+        ms4, calls4 = time_form(False, min(args.warmup, 5), args.steps)
+        four_call = {"ms_per_step": ms4, "tokens_per_s": cfg.T / (ms4 * 1e-3), "per_call_ms": calls4["avg"],
+                     "calls": "moe_route_ws, moe_count_and_permute (maps + x_perm rows), moe_grouped_ffn, "
+                              "moe_combine"}
 
     # Consumers of the load statistic (not part of the step): Algorithm 1 on the layer's own counts,
     # and a speculative predictor pass (a second gate matrix on the same x) on a side stream.
@@ -256,17 +351,16 @@ def main():
     work = algorithmic_work(cfg)
     up_s = per_call_ms["ffn_up"] * 1e-3
     achieved = work["ffn_up_flops"] / up_s / 1e12
-    tr = MEASURED_HBM_TRAFFIC.get(cfg.name)
+    tr = measured_hbm_traffic(cfg.name, ffn_entry(fused))
     roofline = {"bound": "mfma",
-                "kernel": "ffn_mfma_kernel<gated>: part 1 of " +
-                          ("moe_grouped_ffn_ws" if args.ffn_split else
-                           "moe_grouped_ffn_gather" if fused else "moe_grouped_ffn") +
-                          ", main-tile launch plus the remainder launch that overlaps it on a side stream",
+                "kernel": "the gated up-projection GEMM: part 1 of " + ffn_entry(fused),
                 "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
                 "traffic": (tr["read_bytes"] + tr["written_bytes"]) if tr else None,
-                "traffic_unit": "bytes per launch (HBM read + written)",
+                "traffic_unit": "bytes per launch (HBM read + written); null when profiles/ holds no summary "
+                                "taken with this kernel source, entry point and workload",
                 "traffic_detail": tr,
+                "algorithmic_bytes_per_launch": work["ffn_up_bytes"],
                 "flops_per_launch": work["ffn_up_flops"], "avg_launch_ms": per_call_ms["ffn_up"]}
     others = {
         "ffn_down_tflops": work["ffn_down_flops"] / (per_call_ms["ffn_down"] * 1e-3) / 1e12,
@@ -292,16 +386,20 @@ def main():
         "dtype": "bf16" if cfg.dtype == si.BF16 else "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} E={cfg.E} k={cfg.k} F={cfg.F} "
                                f"renorm={cfg.renorm} seed={cfg.seed}, one MoE-layer forward",
-                   "ffn_input": ("x through the permutation map (%s)" % (
-                       "moe_grouped_ffn_ws" if args.ffn_split else "moe_grouped_ffn_gather")) if fused
-                   else "materialised x_perm (%s)" % ("moe_grouped_ffn_ws" if args.ffn_split else "moe_grouped_ffn"),
+                   "ffn_input": ("x through the permutation map (%s)" % ffn_entry(fused)) if fused
+                   else "materialised x_perm (%s)" % ffn_entry(fused),
                    "ffn_split_tiles": bool(args.ffn_split)},
         "ffn_pct_of_bf16_mfma_peak": 100.0 * others["ffn_total_frac_of_mfma_peak"],
         "per_call_ms": per_call_ms, "per_call_ms_min": per_call_ms_min,
         "per_call_ms_median": per_call_ms_median, "roofline": roofline, "other_calls": others,
     }
+    if four_call is not None:
+        out["four_call_form"] = four_call
+        out["four_call_form_ms_per_step"] = four_call["ms_per_step"]
     if consumers is not None:
         out["load_consumers"] = consumers
+    if not args.no_hbm_bound:
+        out["hbm_bound_calls"] = hbm_bound_calls(torch, si, B, layer, st)
     if args.predictor_accuracy:
         import numpy as np
         w_acc = layer.to_device(si.make_layer(
@@ -333,7 +431,7 @@ def main():
                                 buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
         out["ep_simulation"] = ep_sim.simulate(buf, x, w1, w3, w2, args.ep_sim)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, L, min(cfg.T, CPU_SAMPLE_TOKENS.get(cfg.name, 256)))
+        out["cpu_baseline"] = cpu_baseline(cfg, L, cfg.T)
     print(json.dumps(out))
 
 

@@ -44,6 +44,7 @@
 //
 // Generic kernel (fp32, or bf16 shapes whose d or F is not a multiple of 64): a plain
 // LDS-tiled FMA GEMM with fp32 accumulation.
+#include <cstdlib>
 #include <mutex>
 #include <type_traits>
 
@@ -54,7 +55,7 @@ namespace moe {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 
-enum TileMode { TILES_ALL = 0, TILES_MAIN = 1, TILES_SMALL = 2 };
+enum TileMode { TILES_ALL = 0, TILES_MAIN = 1, TILES_SMALL = 2, TILES_EVEN = 3 };
 constexpr int BK_ELEMS = 64;    // K elements per stage of the MFMA kernels
 constexpr int SMALL_ROWS = 64;  // remainders up to this many rows go to the small-tile kernel
 
@@ -85,7 +86,7 @@ struct GemmArgs {
   int split_phase;
 };
 
-constexpr int SPLIT_SLOT_FLOATS = 256 * 256;   // one partial tile (the largest: 256 x 256 fp32)
+constexpr int SPLIT_SLOT_FLOATS = 320 * 256;   // one partial tile (the largest: 320 x 256 fp32)
 constexpr int SPLIT_MAX_PARTS = 4;
 constexpr int SPLIT_MIN_STAGES = 8;            // K stages a part must keep
 
@@ -164,7 +165,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int incl_all = wave_scan_add(n_all), incl_small = wave_scan_add(n_small);
   bool fold = false;                             // small remainders ride in the main launch
   int small_beside = 0;                          // ... or run as small tiles beside this main launch
-  if (mode != TILES_ALL) {
+  if (mode == TILES_MAIN || mode == TILES_SMALL) {
     n_all = __builtin_amdgcn_readlane(incl_all, MOE_WAVE - 1);
     n_small = __builtin_amdgcn_readlane(incl_small, MOE_WAVE - 1);
     // (tile counts fit 32 bits: the host refuses grids beyond 2^31 - 1 blocks, and a grid is an
@@ -262,7 +263,12 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int seg_end = min(__builtin_amdgcn_readlane(found_oe, src), p.rows);
   tc.e = e;
   tc.n_tile = loc / m_tiles;
-  if (mode == TILES_SMALL) {
+  if (mode == TILES_EVEN) {
+    // the segment's 16-row sub-tiles are dealt evenly to its ceil(c / bm) tiles
+    const int sub = (seg_end - seg_begin + 15) / 16;
+    tc.m_begin = seg_begin + (m_idx * sub / m_tiles) * 16;
+    tc.m_end = min(seg_end, seg_begin + ((m_idx + 1) * sub / m_tiles) * 16);
+  } else if (mode == TILES_SMALL) {
     tc.m_begin = seg_begin + ((seg_end - seg_begin) / bm) * bm;
     tc.m_end = seg_end;
   } else {
@@ -317,13 +323,13 @@ constexpr int ffn_lds_bytes(int bm, int nstage) {
 template <int BM, bool GATED, int WM, int WN, int NSTAGE>
 __device__ __forceinline__ void ffn_store_tile(
     const f32x4_t (&acc)[BROWS / WN / 16][BM / WM / 16], const TileCoord& tc, const GemmArgs& p,
-    unsigned char* lds, int wave, int lane, int mi_valid) {
+    unsigned char* lds, int wave, int lane, int mi_valid, int wave_row0) {
   constexpr int NW = WM * WN;
   constexpr int MI = BM / WM / 16;
   constexpr int NI = BROWS / WN / 16;
   constexpr int NIH = GATED ? NI / 2 : NI;
   constexpr int BN_OUT = GATED ? 128 : 256;
-  const int wm = wave / WN, wn = wave % WN;
+  const int wn = wave % WN;
   const int l16 = lane & 15;
   const int N = p.N;
   const int n0 = tc.n_tile * BN_OUT;
@@ -355,7 +361,7 @@ __device__ __forceinline__ void ffn_store_tile(
             make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
-      const int row_base = tc.m_begin + wm * (BM / WM) + mi * 16;
+      const int row_base = tc.m_begin + wave_row0 + mi * 16;
 #pragma unroll
       for (int it = 0; it < 16 / RPI; ++it) {
         const int r = it * RPI + lane / LPR;
@@ -721,7 +727,287 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_mfma_kernel(GemmArgs p) {
             acc[ni][mi];
     return;
   }
-  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid);
+  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid, wm * (BM / WM));
+}
+
+// --------------------------------------------------------------------------------------------
+// Even tiles: an expert's c rows are cut into ceil(c / 320) tiles of (nearly) equal height, a
+// multiple of 16 rows each, so no segment leaves a small remainder that would have to stream the
+// expert's weights once more for a handful of rows: the Mixtral-shaped batch (about 1024 rows
+// per expert) runs as four tiles of 256 or 272 rows per expert, whatever the counts are.
+// Block tile: up to 320 activation rows x 256 weight rows, K step 64, two LDS stages of 72 KiB.
+// 8 waves as 4 (rows) x 2 (weight rows); the tile's 16-row sub-tiles are dealt to the four wave
+// rows as evenly as possible (each takes MIV = 0 .. 5 of them, the first wave rows one more than
+// the last), so a wave holds up to 5 x 8 accumulator tiles.
+//
+// Per k-step a wave multiplies in two parts so that ONE register set holds the fragments of both
+// operands: part 1 takes the first P1 = ceil(MIV / 2) activation sub-tiles against all eight weight
+// sub-tiles; part 2 re-reads those P1 activation fragments for the next k-step, multiplies the
+// other MIV - P1 sub-tiles, re-reading each weight fragment right after its last use, and re-reads
+// the remaining activation fragments at its end.  Every fragment is requested at least 14 MFMAs
+// before it is needed.  LDS reads return in order, so "my fragment has landed" is a count of the
+// reads issued after it.  A stage's barrier sits between the two parts of its second k-step:
+// by then every fragment of the stage is in registers, the stage's buffer takes the loads of the
+// stage after next, and the other buffer (landed: vmcnt(0)) is read from.
+constexpr int EVEN_BM = 320;
+constexpr int EVEN_STAGE = (EVEN_BM + BROWS) * ROWB;
+constexpr int EVEN_LDS = 2 * EVEN_STAGE;
+
+// How the tile's sub-tiles are dealt to wave row wm (of 4): count and first row.
+__device__ __forceinline__ void even_wave_rows(int rows_valid, int wm, int& miv, int& row0) {
+  const int nsub = (rows_valid + 15) >> 4;
+  const int q = nsub >> 2, r = nsub & 3;
+  miv = q + (wm < r ? 1 : 0);
+  row0 = 16 * (wm * q + min(wm, r));
+}
+
+template <bool GATED, bool SPLIT>
+__global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
+  constexpr int NW = 8, WN = 2;
+  constexpr int BM = EVEN_BM, MI = 5, NI = 8;
+  constexpr int NIH = GATED ? NI / 2 : NI;
+  constexpr int STAGE = EVEN_STAGE;
+  constexpr int NLA = BM / 8 / NW;                // 5 activation row groups per wave and stage
+  constexpr int NLW = BROWS / 8 / NW;             // 4 weight row groups
+  constexpr int BN_OUT = GATED ? 128 : 256;
+  extern __shared__ __align__(1024) unsigned char lds[];
+
+  TileCoord tc;
+  if (!decode_tile<SPLIT>(p, tc)) return;
+
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
+  const int wm = wave / WN, wn = wave % WN;
+  const int K = p.K, N = p.N;
+  int kt_first = 0, kt_count = K / BK;
+  if (SPLIT && tc.nparts > 1) {
+    kt_first = tc.part * kt_count / tc.nparts;
+    kt_count = (tc.part + 1) * kt_count / tc.nparts - kt_first;
+  }
+  const int KT = kt_count;
+  const int n0 = tc.n_tile * BN_OUT;
+  const bf16_t* A = static_cast<const bf16_t*>(p.a);
+  const bf16_t* B0 = static_cast<const bf16_t*>(p.b0) + static_cast<int64_t>(tc.e) * N * K;
+  const bf16_t* B1 = GATED ? static_cast<const bf16_t*>(p.b1) + static_cast<int64_t>(tc.e) * N * K
+                           : nullptr;
+  const int rows_valid = min(tc.m_end - tc.m_begin, BM);
+  int miv, row0;
+  even_wave_rows(rows_valid, wm, miv, row0);
+
+  // ---- global -> LDS: 8-row groups of 1 KiB; this wave fills activation groups i*8 + wave
+  //      (only those that hold a valid row) and weight groups i*8 + wave
+  const bool gathered = p.src_assign != nullptr;
+  const int k_first = kt_first * BK;
+  const unsigned char* base_a = reinterpret_cast<const unsigned char*>(
+      (gathered ? A : A + static_cast<int64_t>(tc.m_begin) * K) + k_first);
+  const unsigned char* base_b0 =
+      reinterpret_cast<const unsigned char*>(B0 + static_cast<int64_t>(n0) * K + k_first);
+  const unsigned char* base_b1 =
+      GATED ? reinterpret_cast<const unsigned char*>(B1 + static_cast<int64_t>(n0) * K + k_first)
+            : nullptr;
+  const int groups_valid = (rows_valid + 7) >> 3;
+  const int n_act = min(NLA, max(0, (groups_valid - wave + NW - 1) / NW));   // wave-uniform
+  uint32_t soff_a[NLA], soff_w[NLW];
+#pragma unroll
+  for (int i = 0; i < NLA; ++i) {
+    const int row = (i * NW + wave) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(row);
+    int r = min(row, rows_valid - 1);
+    if (gathered) r = a_row_of(p, tc.m_begin + r);
+    soff_a[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
+  }
+#pragma unroll
+  for (int i = 0; i < NLW; ++i) {
+    const int br = (i * NW + wave) * 8 + (lane >> 3);          // row of the weight tile (BM % 16 == 0)
+    const int chunk = (lane & 7) ^ swz(br);
+    const int r = GATED ? min(br & 127, N - 1 - n0) : min(br, N - 1 - n0);
+    soff_w[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
+  }
+  const __amdgpu_buffer_rsrc_t rs_a =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_a), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_b0 =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_b0), 0, 0x7FFFFFFF, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<unsigned char*>(GATED ? base_b1 : base_b0), 0, 0x7FFFFFFF, 0x00020000);
+  auto issue_stage = [&](int kt, int buf) {
+#pragma unroll
+    for (int i = 0; i < NLA; ++i)
+      if (i < n_act)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rs_a, (__attribute__((address_space(3))) void*)(lds + buf * STAGE + (i * NW + wave) * 1024),
+            16, static_cast<int>(soff_a[i]), kt * ROWB, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NLW; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          (!GATED || i < NLW / 2) ? rs_b0 : rs_b1,
+          (__attribute__((address_space(3))) void*)(lds + buf * STAGE + BM * ROWB + (i * NW + wave) * 1024),
+          16, static_cast<int>(soff_w[i]), kt * ROWB, 0, 0);
+  };
+
+  // ---- LDS addresses of this lane's fragments, per buffer and k-step (chunk order as in
+  //      ffn_mfma_kernel: lane groups 0..3 take chunks 0, 2, 1, 3 of the k-step)
+  const int l16 = lane & 15;
+  const int f = swz(l16);
+  const int kgrp = ((lane >> 4) & 1) * 2 + (lane >> 5);
+  int xa[2][2], wa[2][2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int ko = ((kk * 4 + kgrp) ^ f) << 4;
+      xa[b][kk] = b * STAGE + (row0 + l16) * ROWB + ko;
+      wa[b][kk] = b * STAGE + (BM + wn * (NIH * 16) + l16) * ROWB + ko;
+    }
+
+  f32x4_t acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+#define MOE_RD(dst, addr, off) \
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
+#define MOE_MFMA(c, w, x) \
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
+#define MOE_W_OFF(ni) ((GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
+  static_assert(MOE_W_OFF(NI - 1) < 65536 && (MI - 1) * 16 * ROWB < 65536, "ds_read offset field");
+
+  auto k_loop = [&](auto miv_c) {
+    constexpr int MIV = decltype(miv_c)::value;
+    constexpr int P1 = (MIV + 1) / 2, P2 = MIV - P1;
+    bf16x8_t x[MI], w[NI];
+    // the fragments of a k-step are always requested in the order x[0..P1), w[0..NI), x[P1..MIV)
+    auto part1 = [&]() {
+      if constexpr (MIV > 0) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+          asm volatile("s_waitcnt lgkmcnt(%0)" ::"i"(NI - 1 - ni + P2) : "memory");
+#pragma unroll
+          for (int mi = 0; mi < P1; ++mi) MOE_MFMA(acc[ni][mi], w[ni], x[mi]);
+        }
+      }
+    };
+    auto part2 = [&](int xn, int wnx) {
+      if constexpr (MIV > 0) {
+#pragma unroll
+        for (int mi = 0; mi < P1; ++mi) MOE_RD(x[mi], xn, mi * 16 * ROWB);
+        if constexpr (P2 > 0) asm volatile("s_waitcnt lgkmcnt(%0)" ::"i"(P1) : "memory");
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+#pragma unroll
+          for (int mi = P1; mi < MIV; ++mi) MOE_MFMA(acc[ni][mi], w[ni], x[mi]);
+          MOE_RD(w[ni], wnx, MOE_W_OFF(ni));
+        }
+#pragma unroll
+        for (int mi = P1; mi < MIV; ++mi) MOE_RD(x[mi], xn, mi * 16 * ROWB);
+      }
+    };
+    auto stage = [&](int kt, auto par_c) {
+      constexpr int PAR = decltype(par_c)::value;
+      part1();
+      part2(xa[PAR][1], wa[PAR][1]);
+      part1();
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      if (kt + 2 < KT) issue_stage(kt + 2, PAR);
+      // after the last stage these reads return stale LDS and go unused
+      part2(xa[PAR ^ 1][0], wa[PAR ^ 1][0]);
+    };
+    // prologue: stages 0 and 1 requested; stage 0 must have landed for every wave
+    issue_stage(0, 0);
+    if (KT > 1) {
+      issue_stage(1, 1);
+      switch (n_act) {                              // this wave's loads of stage 1 may still fly
+        case 0: wait_vmcnt<NLW>(); break;
+        case 1: wait_vmcnt<NLW + 1>(); break;
+        case 2: wait_vmcnt<NLW + 2>(); break;
+        case 3: wait_vmcnt<NLW + 3>(); break;
+        case 4: wait_vmcnt<NLW + 4>(); break;
+        default: wait_vmcnt<NLW + 5>(); break;
+      }
+    } else {
+      wait_vmcnt<0>();
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if constexpr (MIV > 0) {
+#pragma unroll
+      for (int mi = 0; mi < P1; ++mi) MOE_RD(x[mi], xa[0][0], mi * 16 * ROWB);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) MOE_RD(w[ni], wa[0][0], MOE_W_OFF(ni));
+#pragma unroll
+      for (int mi = P1; mi < MIV; ++mi) MOE_RD(x[mi], xa[0][0], mi * 16 * ROWB);
+    }
+    int kt = 0;
+    for (; kt + 2 <= KT; kt += 2) {
+      stage(kt, std::integral_constant<int, 0>{});
+      stage(kt + 1, std::integral_constant<int, 1>{});
+    }
+    if (kt < KT) stage(kt, std::integral_constant<int, 0>{});
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the unused reads of the last stage
+    // the compiler's hazard handling does not see asm MFMAs: let the last results retire
+    // before ordinary VALU code reads the accumulators
+    asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
+  };
+  switch (miv) {                                    // wave-uniform
+    case 0: k_loop(std::integral_constant<int, 0>{}); break;
+    case 1: k_loop(std::integral_constant<int, 1>{}); break;
+    case 2: k_loop(std::integral_constant<int, 2>{}); break;
+    case 3: k_loop(std::integral_constant<int, 3>{}); break;
+    case 4: k_loop(std::integral_constant<int, 4>{}); break;
+    default: k_loop(std::integral_constant<int, 5>{}); break;
+  }
+#undef MOE_RD
+#undef MOE_MFMA
+#undef MOE_W_OFF
+
+  if (SPLIT && tc.nparts > 1) {
+    constexpr int NT = NW * MOE_WAVE;
+    float* mine = p.split_ws + static_cast<int64_t>(tc.pslot) * SPLIT_SLOT_FLOATS;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi)
+        *reinterpret_cast<f32x4_t*>(mine + ((ni * MI + mi) * NT + static_cast<int>(threadIdx.x)) * 4) =
+            acc[ni][mi];
+    return;
+  }
+  ffn_store_tile<BM, GATED, 4, WN, 2>(acc, tc, p, lds, wave, lane, miv, row0);
+}
+
+// The launch after ffn_even_kernel<.., SPLIT>: adds the parts of every split tile in part order and
+// stores it (see ffn_sum_parts_kernel).
+template <bool GATED>
+__global__ __launch_bounds__(512) void ffn_even_sum_parts_kernel(GemmArgs p) {
+  constexpr int NW = 8, WN = 2, MI = 5, NI = 8;
+  constexpr int NT = NW * MOE_WAVE;
+  extern __shared__ __align__(1024) unsigned char lds[];
+  TileCoord tc;
+  if (!decode_tile<true>(p, tc)) return;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
+  int miv, row0;
+  even_wave_rows(min(tc.m_end - tc.m_begin, EVEN_BM), wave / WN, miv, row0);
+  f32x4_t acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) acc[ni][mi] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  const float* first = p.split_ws + static_cast<int64_t>(tc.pslot) * SPLIT_SLOT_FLOATS;
+  for (int q = 0; q < tc.nparts; ++q) {
+    const float* src = first + static_cast<int64_t>(q) * SPLIT_SLOT_FLOATS;
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(
+            src + ((ni * MI + mi) * NT + static_cast<int>(threadIdx.x)) * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc[ni][mi][u] += v[u];
+      }
+  }
+  ffn_store_tile<EVEN_BM, GATED, 4, WN, 2>(acc, tc, p, lds, wave, lane, miv, row0);
 }
 
 // The launch after a GEMM whose tiles may have been split: block (xcd, t) adds the parts of split
@@ -759,7 +1045,7 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_sum_parts_kernel(GemmArgs p)
         for (int u = 0; u < 4; ++u) acc[ni][mi][u] += v[u];
       }
   }
-  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid);
+  ffn_store_tile<BM, GATED, WM, WN, NSTAGE>(acc, tc, p, lds, wave, lane, mi_valid, wm * (BM / WM));
 }
 
 // --------------------------------------------------------------------------------------------
@@ -903,6 +1189,38 @@ static int launch_mfma_as(GemmArgs a, int mode, int bm_main, int64_t A, hipStrea
   return rc;
 }
 
+template <bool GATED, bool SPLIT>
+static int launch_even_as(GemmArgs a, int64_t A, hipStream_t st) {
+  static LdsOnce once;
+  if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(ffn_even_kernel<GATED, SPLIT>), EVEN_LDS) !=
+      MOE_OK)
+    return MOE_ERR_HIP;
+  a.mode = TILES_EVEN;
+  a.bm_main = EVEN_BM;
+  a.split_phase = 0;
+  if (!SPLIT) a.split_ws = nullptr;
+  int64_t grid = max_m_tiles(A, a.E, EVEN_BM, TILES_EVEN) * a.n_tiles;
+  if (grid == 0) return MOE_OK;
+  grid = (grid + 7) / 8 * 8;
+  const int cu8 = (a.n_cu > 0 ? a.n_cu : 256) / 8 * 8;
+  if (SPLIT) grid += cu8;
+  if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((ffn_even_kernel<GATED, SPLIT>), dim3(static_cast<unsigned>(grid)), dim3(512),
+                     EVEN_LDS, st, a);
+  int rc = launch_status();
+  if (SPLIT && rc == MOE_OK) {
+    static LdsOnce once_sum;
+    if (ensure_dynamic_lds(once_sum, reinterpret_cast<const void*>(ffn_even_sum_parts_kernel<GATED>),
+                           EVEN_LDS) != MOE_OK)
+      return MOE_ERR_HIP;
+    a.split_phase = 1;
+    hipLaunchKernelGGL((ffn_even_sum_parts_kernel<GATED>), dim3(static_cast<unsigned>(cu8)), dim3(512),
+                       EVEN_LDS, st, a);
+    rc = launch_status();
+  }
+  return rc;
+}
+
 // `split`: this launch may use the workspace for split tiles if the caller brought one.  Only
 // GEMMs with a long reduction do: a part must be worth the exchange (one 256 KiB store per part,
 // the summing launch), and a tile of fewer than 96 stages is too short for that (measured: the
@@ -980,6 +1298,17 @@ static int mfma_ffn(const GemmArgs& g1, const GemmArgs& g2, bool up, bool down, 
     // shape: 64 rows per expert 0.85 -> 0.63 ms against 128-row main tiles plus remainders.)
     if (up && (rc = launch_mfma<64, true, 2, 4, 4>(g1, TILES_ALL, 64, A, st, true)) != MOE_OK) return rc;
     if (down) rc = launch_mfma<64, false, 2, 4, 4>(g2, TILES_ALL, 64, A, st, true);
+    return rc;
+  }
+  static const int form = [] { const char* e = getenv("MOE_FFN_FORM"); return e ? atoi(e) : 1; }();
+  if (form == 1) {
+    auto launch = [&](const GemmArgs& g, auto gated_c) {
+      constexpr bool G = decltype(gated_c)::value;
+      return g.split_ws && g.K >= SPLIT_MIN_K ? launch_even_as<G, true>(g, A, st)
+                                              : launch_even_as<G, false>(g, A, st);
+    };
+    if (up && (rc = launch(g1, std::true_type{})) != MOE_OK) return rc;
+    if (down) rc = launch(g2, std::false_type{});
     return rc;
   }
   std::lock_guard<std::mutex> lock(g_side_mutex);
