@@ -137,12 +137,9 @@ int moe_count_and_permute_static(const moe_shape_t* shape, const void* x, const 
  * x_perm [T*k,d]; w1, w3 [E,F,d]; w2 [E,d,F]; h [T*k,F] (caller-provided scratch,
  * holds the activations on return); y_perm [T*k,d]; all in `dtype`; offsets [E+1]
  * int32 on the device (read by the kernels; no host round trip).
- * Streams: for layers with large experts (T*k/E >= 128) part of the work is enqueued on
- * one library-owned side stream per device (default priority, created at first use, kept
- * for the life of the process), forked from `hip_stream` with an event and joined back with
- * another before the call returns.  For the caller all work is ordered on `hip_stream` as
- * usual, and a stream capture of `hip_stream` records the fork and join as graph edges.
- * Calls from several host threads are safe; their enqueue sequences are serialised.
+ * Two launches (one per GEMM) on `hip_stream`; the library keeps no stream, event or other state
+ * of its own, so calls from several host threads or on several streams are independent, and a
+ * stream capture records exactly these launches.
  */
 int moe_grouped_ffn(const moe_shape_t* shape, const void* x_perm, const int32_t* offsets,
                     const void* w1, const void* w3, const void* w2, void* h, void* y_perm,
@@ -191,7 +188,7 @@ int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x, const i
  *                   otherwise x [T, d] and the map, as for moe_grouped_ffn_gather
  *   parts           1 = up-projection only, 2 = down-projection only, 3 = both
  *   workspace       device memory, 16-byte aligned, at least moe_ffn_workspace_bytes() bytes
- *                   (64 MiB on a 256-CU device), contents irrelevant; or NULL (then exactly
+ *                   (80 MiB on a 256-CU device), contents irrelevant; or NULL (then exactly
  *                   moe_grouped_ffn / moe_grouped_ffn_gather).  Calls that share a workspace
  *                   must not overlap in time.
  * Errors as moe_grouped_ffn; MOE_ERR_WORKSPACE if workspace_bytes is too small.

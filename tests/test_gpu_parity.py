@@ -411,18 +411,38 @@ def test_grouped_ffn_matches_oracle(case):
 
 
 @pytest.mark.parametrize("d,F", [(64, 704), (128, 640), (192, 576), (256, 512), (320, 448), (384, 384)])
-def test_grouped_ffn_every_stage_count_of_the_main_tile_ring(d, F):
+def test_grouped_ffn_every_stage_count_of_the_two_stage_pipeline(d, F):
     # K stages of 64 elements: the up-projection takes d / 64 of them and the down-projection F / 64,
-    # so the six cases run the main tile's five-slot operand ring over 1 to 11 stages (prologue only,
-    # every tail length, several turns of the ring); each expert has full 256-row tiles, one partial
-    # main tile whose waves take the other code path of the same block, or a small remainder
+    # so the six cases run the even tiles' two-buffer pipeline over 1 to 11 stages (prologue only,
+    # odd and even counts); the experts hold one tile of 256 rows (every wave four sub-tiles), one of
+    # 300 rows (19 sub-tiles: waves with five and with four) and two tiles of 224 rows (waves with
+    # four and with three sub-tiles)
     cfg = si.small_config(T=1000, d=d, E=3, k=1, F=F)
     L = si.make_layer(cfg)
     idx = np.zeros((cfg.T, 1), dtype=np.int32)
-    idx[:256] = 0            # exactly one full tile
-    idx[256:256 + 300] = 1   # one full tile and a small remainder (44 rows)
-    idx[556:] = 2            # one full tile and a partial main tile (188 rows)
+    idx[:256] = 0
+    idx[256:256 + 300] = 1
+    idx[556:] = 2
     check_ffn(cfg, L, idx)
+
+
+@pytest.mark.parametrize("rows", [1, 15, 16, 17, 47, 64, 65, 130, 255, 257, 319, 320, 321, 336, 641, 1000])
+def test_grouped_ffn_even_tiles_every_wave_share(rows):
+    # one hot expert with `rows` rows among experts of 128 rows (so that the mean stays above the
+    # even tiles' threshold): its tiles give the waves every count of sub-tiles from 0 to 5, tiles
+    # below and at the 320-row limit, and segments that need two or three tiles; both ways of
+    # sharing the loads among the waves (the threshold on the mean rows per expert picks one)
+    for E, others in ((3, 600), (9, 150)):             # mean rows per expert above / below 384
+        cfg = si.small_config(T=rows + (E - 1) * others, d=128, E=E, k=1, F=256, seed=rows + E)
+        L = si.make_layer(cfg)
+        idx = np.zeros((cfg.T, 1), dtype=np.int32)
+        idx[:rows] = 1
+        pos = rows
+        for e in range(E):
+            if e != 1:
+                idx[pos:pos + others] = e
+                pos += others
+        check_ffn(cfg, L, idx)
 
 
 SPLIT_CASES = [
@@ -575,9 +595,8 @@ def test_layer_end_to_end(cfg):
 
 
 def test_layer_replays_from_a_hip_graph():
-    """The four calls captured into one HIP graph (the grouped FFN forks its remainder launches to
-    a side stream and joins them back, which the capture must follow) replay to the eager bits.
-    Eager work and synchronisations sit between the replays; no call allocates or clears memory."""
+    """The four calls captured into one HIP graph replay to the eager bits.  Eager work and
+    synchronisations sit between the replays; no call allocates or clears memory."""
     cfg = si.small_config("bf16_graph", T=1400, d=128, E=2, k=2, F=256)
     L = si.make_layer(cfg)
     buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
@@ -690,10 +709,9 @@ def test_ffn_gather_rejects_missing_map_and_survives_bad_entries():
 
 
 def test_two_host_threads_on_two_streams():
-    """The header promises that calls from several host threads are safe (the grouped FFN shares one
-    side stream and event pair per device under a mutex).  Two threads, each with its own stream
-    and buffers, run the layer repeatedly at the same time; every result equals the one obtained
-    alone."""
+    """The header promises that calls from several host threads are independent (the library keeps
+    no state of its own).  Two threads, each with its own stream and buffers, run the layer
+    repeatedly at the same time; every result equals the one obtained alone."""
     import threading
     cfgs = [si.small_config("thr_a", T=1400, d=128, E=2, k=2, F=256),
             si.small_config("thr_b", T=900, d=256, E=4, k=2, F=128, seed=11)]
