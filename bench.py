@@ -203,7 +203,7 @@ def main():
         return ("moe_grouped_ffn_ws" if args.ffn_split else
                 "moe_grouped_ffn_gather" if fused else "moe_grouped_ffn")
 
-    def make_calls(fused):
+    def make_calls(fused, combine_in_ffn=False):
         def call_route():
             B.moe_route_ws(sh, x, wg, bias, buf.topk_idx, buf.topk_w, None, buf.workspace, buf.ws_bytes, st)
 
@@ -213,7 +213,11 @@ def main():
                                     buf.ws_bytes, st)
 
         def call_ffn(part=None):
-            if args.ffn_split:
+            if combine_in_ffn:
+                if part in (None, 2):      # (its two GEMMs cannot be called apart: timed as the down call)
+                    B.moe_grouped_ffn_combine_k1(sh, x, buf.src_assign, buf.offsets, w1, w3, w2, buf.topk_w,
+                                                 buf.h, buf.y, st)
+            elif args.ffn_split:
                 B.moe_grouped_ffn_ws(sh, x if fused else buf.x_perm, buf.src_assign if fused else None,
                                      buf.offsets, w1, w3, w2, buf.h, buf.y_perm, 3 if part is None else part,
                                      buf.ffn_ws, buf.ffn_ws_bytes, st)
@@ -228,14 +232,15 @@ def main():
                 B.moe_grouped_ffn_part(sh, buf.x_perm, buf.offsets, w1, w3, w2, buf.h, buf.y_perm, part, st)
 
         def call_combine():
-            B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
+            if not combine_in_ffn:
+                B.moe_combine(sh, buf.y_perm, buf.dst_row, buf.topk_w, buf.y, st)
 
         return call_route, call_permute, call_ffn, call_combine
 
-    def time_form(fused, warmup, steps):
+    def time_form(fused, warmup, steps, combine_in_ffn=False):
         """ms per step of the whole path (wall clock around `steps` steps), and the average, minimum and
         median duration of every call from HIP events recorded on the launch stream."""
-        call_route, call_permute, call_ffn, call_combine = make_calls(fused)
+        call_route, call_permute, call_ffn, call_combine = make_calls(fused, combine_in_ffn)
         for _ in range(warmup):
             call_route(), call_permute(), call_ffn(), call_combine()
         torch.cuda.synchronize()
@@ -284,6 +289,14 @@ def main():
         four_call = {"ms_per_step": ms4, "tokens_per_s": cfg.T / (ms4 * 1e-3), "per_call_ms": calls4["avg"],
                      "calls": "moe_route_ws, moe_count_and_permute (maps + x_perm rows), moe_grouped_ffn, "
                               "moe_combine"}
+
+    # layers with one expert per token: the combine folded into the down-projection's store
+    k1_form = None
+    if cfg.k == 1 and cfg.dtype == si.BF16 and not args.ffn_split:
+        ms1, calls1 = time_form(True, min(args.warmup, 5), args.steps, combine_in_ffn=True)
+        k1_form = {"ms_per_step": ms1, "tokens_per_s": cfg.T / (ms1 * 1e-3),
+                   "grouped_ffn_and_combine_ms": calls1["avg"]["ffn_down"],
+                   "calls": "moe_route_ws, moe_count_and_permute (maps only), moe_grouped_ffn_combine_k1"}
 
     # Consumers of the load statistic (not part of the step): Algorithm 1 on the layer's own counts,
     # and a speculative predictor pass (a second gate matrix on the same x) on a side stream.
@@ -396,6 +409,8 @@ def main():
     if four_call is not None:
         out["four_call_form"] = four_call
         out["four_call_form_ms_per_step"] = four_call["ms_per_step"]
+    if k1_form is not None:
+        out["combine_in_ffn_form"] = k1_form
     if consumers is not None:
         out["load_consumers"] = consumers
     if not args.no_hbm_bound:

@@ -176,6 +176,24 @@ int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x, const i
                                 const void* w2, void* h, void* y_perm, int part, void* hip_stream);
 
 /*
+ * Grouped FFN and combine in one call for layers that activate ONE expert per token (k = 1:
+ * Llama-4-Scout in Table 1).  With k = 1 the gather that collects and reorders the expert outputs
+ * (Section 2.2) has nothing to add up: y[t] = topk_w[t] * E_idx[t](x[t]), so the down-projection
+ * stores row r of its result, scaled, straight to y[src_assign[r]] (fp32 product, one rounding),
+ * and neither x_perm nor y_perm exists; moe_combine is not called.  x [T,d] and src_assign as for
+ * moe_grouped_ffn_gather; topk_w [T] fp32 (the routing weights of moe_route); h [T,F] scratch;
+ * y [T,d].  y differs from moe_grouped_ffn_gather + moe_combine by at most one rounding of the
+ * storage type (those round y_perm first).  src_assign must be a permutation of 0..T-1 for every
+ * row of y to be written; entries outside give unspecified rows (never out-of-bounds accesses).
+ * MOE_ERR_UNSUPPORTED if shape->k != 1.  Layers with k >= 2 keep the two calls: the k
+ * contributions to a token come from different experts' tiles, and adding them in the stores would
+ * need atomics whose order (and with it the rounding of y) depends on scheduling.
+ */
+int moe_grouped_ffn_combine_k1(const moe_shape_t* shape, const void* x, const int32_t* src_assign,
+                               const int32_t* offsets, const void* w1, const void* w3, const void* w2,
+                               const float* topk_w, void* h, void* y, void* hip_stream);
+
+/*
  * moe_grouped_ffn / moe_grouped_ffn_gather (Section 3.2) with a workspace that lets the bf16 MFMA
  * kernels cut tiles along the reduction dimension.  A GEMM's tiles run in rounds of the chip's
  * compute units; when the last round is at most half full, each of its tiles is computed as 2 to

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = ("moe_workspace_bytes", "moe_route", "moe_route_ws", "moe_count_and_permute",
            "moe_count_and_permute_static", "moe_grouped_ffn",
            "moe_grouped_ffn_part", "moe_grouped_ffn_gather",
-           "moe_grouped_ffn_gather_part", "moe_ffn_workspace_bytes", "moe_grouped_ffn_ws", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
+           "moe_grouped_ffn_gather_part", "moe_grouped_ffn_combine_k1", "moe_ffn_workspace_bytes", "moe_grouped_ffn_ws", "moe_combine", "moe_scale_replicas", "moe_replica_segments",
            "moe_place_replicas",
            "moe_strerror")
 MOE_MAX_EXTRA_REPLICAS = 65536
@@ -64,6 +64,7 @@ def load():
     lib.moe_grouped_ffn_gather.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, vp]
     lib.moe_grouped_ffn_gather_part.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp,
                                                 ctypes.c_int, vp]
+    lib.moe_grouped_ffn_combine_k1.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, f32p, vp, vp, vp]
     lib.moe_ffn_workspace_bytes.argtypes = [shp, ctypes.POINTER(ctypes.c_size_t)]
     lib.moe_grouped_ffn_ws.argtypes = [shp, vp, i32p, i32p, vp, vp, vp, vp, vp, ctypes.c_int, vp,
                                        ctypes.c_size_t, vp]
@@ -175,6 +176,13 @@ def moe_grouped_ffn_gather_part(shape, x, src_assign, offsets, w1, w3, w2, h, y_
            load().moe_grouped_ffn_gather_part(ctypes.byref(shape), _ptr(x), _ptr(src_assign),
                                               _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(h),
                                               _ptr(y_perm), int(part), _stream(stream)))
+
+
+def moe_grouped_ffn_combine_k1(shape, x, src_assign, offsets, w1, w3, w2, topk_w, h, y, stream=None):
+    _check("moe_grouped_ffn_combine_k1",
+           load().moe_grouped_ffn_combine_k1(ctypes.byref(shape), _ptr(x), _ptr(src_assign),
+                                             _ptr(offsets), _ptr(w1), _ptr(w3), _ptr(w2), _ptr(topk_w),
+                                             _ptr(h), _ptr(y), _stream(stream)))
 
 
 def moe_ffn_workspace_bytes(shape: MoeShape) -> int:

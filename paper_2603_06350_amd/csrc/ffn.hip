@@ -71,6 +71,12 @@ struct GemmArgs {
   // up the parts of every split tile and stores it.
   float* split_ws;
   int split_phase;
+  // Scattered, scaled output (plain GEMM of a k = 1 layer: the combine folded into the store):
+  // GEMM row r goes to row out_map[r] of `out`, multiplied by out_scale[out_map[r]] before the
+  // one rounding.  nullptr = row r of `out`, unscaled.
+  const int32_t* out_map;
+  const float* out_scale;
+  int out_rows;     // rows of `out` (mapped row numbers are clamped to it)
 };
 
 constexpr int SPLIT_SLOT_FLOATS = 320 * 256;   // one partial tile (the largest: 320 x 256 fp32)
@@ -271,9 +277,14 @@ __device__ __forceinline__ void ffn_store_tile(const f32x4_t (&acc)[NI][MI], con
   unsigned char* region = lds + wave * (16 * PITCH);
   bf16_t* out = static_cast<bf16_t*>(p.out);
   const int col0 = n0 + wn * CW;                  // first output column of this wave
+  const int32_t* out_map = GATED ? nullptr : p.out_map;   // uniform
+  auto mapped_row = [&](int gr) { return min(max(out_map[min(gr, tc.m_end - 1)], 0), p.out_rows - 1); };
 #pragma unroll
   for (int mi = 0; mi < MI; ++mi) {
     if (mi < mi_valid) {                          // wave-uniform
+      const int row_base = tc.m_begin + wave_row0 + mi * 16;
+      // this lane's accumulators belong to row lane%16 of the sub-tile
+      const float scale = out_map ? p.out_scale[mapped_row(row_base + l16)] : 1.f;
 #pragma unroll
       for (int ni = 0; ni < NIH; ++ni) {
         float o[4];
@@ -282,22 +293,23 @@ __device__ __forceinline__ void ffn_store_tile(const f32x4_t (&acc)[NI][MI], con
           if (GATED)
             o[u] = silu_mul(acc[ni][mi][u], acc[GATED ? ni + NIH : ni][mi][u]);
           else
-            o[u] = acc[ni][mi][u];
+            o[u] = out_map ? acc[ni][mi][u] * scale : acc[ni][mi][u];
         }
         const int c = ni * 16 + 4 * (lane >> 4);
         *reinterpret_cast<uint2*>(region + l16 * PITCH + c * 2) =
             make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // same wave: writes land before the reads
-      const int row_base = tc.m_begin + wave_row0 + mi * 16;
 #pragma unroll
       for (int it = 0; it < 16 / RPI; ++it) {
         const int r = it * RPI + lane / LPR;
         const int c = (lane % LPR) * 8;           // first column of this lane's 16 bytes
         const uint4 v = *reinterpret_cast<const uint4*>(region + r * PITCH + c * 2);
         const int gr = row_base + r;
-        if (gr < tc.m_end && col0 + c < N)
-          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(gr) * N + col0 + c) = v;
+        if (gr < tc.m_end && col0 + c < N) {
+          const int dst = out_map ? mapped_row(gr) : gr;
+          *reinterpret_cast<uint4*>(out + static_cast<int64_t>(dst) * N + col0 + c) = v;
+        }
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // reads done before the region is reused
     }
@@ -875,10 +887,16 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
     __syncthreads();
   }
   T* out = static_cast<T*>(p.out);
+  const int32_t* out_map = GATED ? nullptr : p.out_map;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int gr = tc.m_begin + ty * 4 + i;
+    int gr = tc.m_begin + ty * 4 + i;
     if (gr >= tc.m_end) continue;
+    float scale = 1.f;
+    if (out_map) {
+      gr = min(max(out_map[gr], 0), p.out_rows - 1);
+      scale = p.out_scale[gr];
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int c = n0 + tx * 4 + j;
@@ -888,7 +906,7 @@ __global__ __launch_bounds__(256) void ffn_generic_kernel(GemmArgs p) {
           const float g = acc[0][i][j];
           v = g / (1.0f + expf(-g)) * acc[GATED ? 1 : 0][i][j];
         } else {
-          v = acc[0][i][j];
+          v = out_map ? acc[0][i][j] * scale : acc[0][i][j];
         }
         st_elem(out + static_cast<int64_t>(gr) * N + c, v);
       }
@@ -1016,10 +1034,12 @@ static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, hip
 
 // parts: bit 0 = gated up-projection (h), bit 1 = down-projection (y_perm)
 // x_perm [T*k, d] with src_assign == nullptr, or x [T, d] with the src_assign map of the dispatch
+// combine_w != nullptr (k = 1 layers only): y_perm is y [T, d]; row r of the down-projection is
+// stored to y[src_assign[r]] times combine_w[src_assign[r]]
 static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* src_assign,
                             const int32_t* offsets, const void* w1, const void* w3, const void* w2,
                             void* h, void* y_perm, int parts, void* hip_stream,
-                            void* split_ws = nullptr) {
+                            void* split_ws = nullptr, const float* combine_w = nullptr) {
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
@@ -1037,9 +1057,10 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   const int n_cu = device_cu_count();
   GemmArgs g1{x_perm, w1, w3, h, offsets, E, d, F, 0, static_cast<int>(A), TILES_FIXED, 64,
               src_assign, shape->k, src_assign ? shape->T : static_cast<int>(A), n_cu,
-              static_cast<float*>(split_ws), 0};
+              static_cast<float*>(split_ws), 0, nullptr, nullptr, 0};
   GemmArgs g2{h, w2, nullptr, y_perm, offsets, E, F, d, 0, static_cast<int>(A), TILES_FIXED, 64,
-              nullptr, 1, static_cast<int>(A), n_cu, static_cast<float*>(split_ws), 0};
+              nullptr, 1, static_cast<int>(A), n_cu, static_cast<float*>(split_ws), 0,
+              combine_w ? src_assign : nullptr, combine_w, shape->T};
   const bool up = parts & 1, down = parts & 2;
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
@@ -1106,6 +1127,17 @@ extern "C" int moe_grouped_ffn_gather(const moe_shape_t* shape, const void* x,
                                       void* y_perm, void* hip_stream) {
   if (!src_assign) return MOE_ERR_INVALID_ARG;
   return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, 3, hip_stream);
+}
+
+extern "C" int moe_grouped_ffn_combine_k1(const moe_shape_t* shape, const void* x,
+                                          const int32_t* src_assign, const int32_t* offsets,
+                                          const void* w1, const void* w3, const void* w2,
+                                          const float* topk_w, void* h, void* y, void* hip_stream) {
+  if (!shape) return MOE_ERR_INVALID_ARG;
+  if (shape->k != 1) return MOE_ERR_UNSUPPORTED;
+  if (!src_assign || !topk_w) return MOE_ERR_INVALID_ARG;
+  return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y, 3, hip_stream, nullptr,
+                               topk_w);
 }
 
 extern "C" int moe_grouped_ffn_gather_part(const moe_shape_t* shape, const void* x,

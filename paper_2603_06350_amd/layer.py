@@ -54,16 +54,23 @@ class MoeBuffers:
         self.ffn_ws = torch.empty((self.ffn_ws_bytes,), dtype=torch.uint8, **kw) if split_tiles else None
 
     def forward(self, x, w_gate, w1, w3, w2, gate_bias=None, stream=None, export_scores=False,
-                gather_in_ffn=False):
+                gather_in_ffn=False, combine_in_ffn=False):
         """The whole hot path: route -> count+permute -> grouped FFN -> combine.
         gather_in_ffn: the up-projection reads x through the permutation map and x_perm is not
-        materialised (same results, bit for bit)."""
+        materialised (same results, bit for bit).
+        combine_in_ffn (k = 1 layers): the down-projection stores the weighted rows straight to y
+        (moe_grouped_ffn_combine_k1); x_perm, y_perm and moe_combine are not used."""
         s = torch.cuda.current_stream() if stream is None else stream
         B.moe_route_ws(self.shape, x, w_gate, gate_bias, self.topk_idx, self.topk_w,
                        self.scores if export_scores else None, self.workspace, self.ws_bytes, s)
         B.moe_count_and_permute(self.shape, x, self.topk_idx, self.counts, self.offsets,
-                                self.dst_row, self.src_assign, None if gather_in_ffn else self.x_perm,
+                                self.dst_row, self.src_assign,
+                                None if (gather_in_ffn or combine_in_ffn) else self.x_perm,
                                 self.workspace, self.ws_bytes, s)
+        if combine_in_ffn:
+            B.moe_grouped_ffn_combine_k1(self.shape, x, self.src_assign, self.offsets, w1, w3, w2,
+                                         self.topk_w, self.h, self.y, s)
+            return self.y
         if self.ffn_ws is not None:
             B.moe_grouped_ffn_ws(self.shape, x if gather_in_ffn else self.x_perm,
                                  self.src_assign if gather_in_ffn else None, self.offsets, w1, w3, w2,

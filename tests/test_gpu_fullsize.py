@@ -174,6 +174,19 @@ def test_full_size_sampled(name, n_tokens):
     # property that holds at any size: all of y is finite and no row was left unwritten
     y = buf.y.float()
     assert torch.isfinite(y).all() and (y.abs().amax(dim=1) > 0).all()
+    if cfg.k == 1:
+        # one expert per token: the form with the combine folded into the down-projection's store
+        # gives, at full size, the two-call form's y up to one rounding of the storage type
+        print("the combine folded into the grouped FFN", flush=True)
+        dev = {n: layer.to_device(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")}
+        two_calls = buf.y.float().clone()
+        buf.y.zero_()
+        buf.forward(dev["x"], dev["w_gate"], dev["w1"], dev["w3"], dev["w2"],
+                    gate_bias=layer.to_device(L["gate_bias"]), combine_in_ffn=True)
+        torch.cuda.synchronize()
+        fused = buf.y.float()
+        assert bool((fused - two_calls).abs().le(2.0 ** -7 * two_calls.abs() + 1e-30).all())
+        assert (fused.abs().amax(dim=1) > 0).all()
 
 
 @pytest.mark.parametrize("name", ["tiny", "decode"])

@@ -746,3 +746,50 @@ def test_two_host_threads_on_two_streams():
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads), "a thread did not finish"
     assert not errors, errors
+
+
+# ----------------------------------------------------------------------------- k = 1: combine in the FFN
+@pytest.mark.parametrize("cfg", [
+    si.small_config("k1_even", T=1500, d=256, E=3, k=1, F=384, renorm=0),       # even tiles, several per expert
+    si.small_config("k1_ring", T=300, d=128, E=8, k=1, F=256, renorm=0, seed=5),  # ring tiles
+    si.small_config("k1_odd", T=200, d=96, E=4, k=1, F=160, renorm=0, seed=6),  # bf16, no MFMA shape
+    si.small_config("k1_f32", T=150, d=64, E=4, k=1, F=96, dtype=si.F32, renorm=0, seed=7),
+], ids=lambda c: c.name)
+def test_ffn_with_the_combine_folded_in_for_one_expert_per_token(cfg):
+    """moe_grouped_ffn_combine_k1 against the oracle's layer and against the two-call form (which
+    rounds y_perm before the weight is applied: at most one more rounding)."""
+    L = si.make_layer(cfg)
+    ref = orc.moe_layer(L["x"], L["w_gate"], L["w1"], L["w3"], L["w2"], cfg.k, cfg.renorm, L["gate_bias"])
+    args = [dev(L[n]) for n in ("x", "w_gate", "w1", "w3", "w2")]
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    buf.forward(*args, gather_in_ffn=True)
+    torch.cuda.synchronize()
+    two_calls = orc.to_f64(host(buf.y))
+    h_two = host(buf.h).copy()
+    buf.y.zero_()
+    buf.y_perm.fill_(7)                              # must stay untouched
+    buf.forward(*args, combine_in_ffn=True)
+    torch.cuda.synchronize()
+    fused = orc.to_f64(host(buf.y))
+    assert np.array_equal(host(buf.topk_idx), ref["topk_idx"])
+    assert np.array_equal(host(buf.h), h_two)
+    assert (orc.to_f64(host(buf.y_perm)) == 7).all()
+    tol = tol_of(cfg.dtype)
+    assert rel_err(fused, ref["y"]) <= tol
+    row_scale = np.abs(ref["y"]).max(axis=1) + 1e-30
+    assert (np.abs(fused - ref["y"]).max(axis=1) / row_scale).max() <= 4 * tol
+    # one rounding of the storage type apart from the two-call form, element by element
+    ulp = 2.0 ** -8 if cfg.dtype == si.BF16 else 2.0 ** -23
+    assert np.all(np.abs(fused - two_calls) <= 2 * ulp * np.abs(two_calls) + 1e-30)
+    # every row of y was written
+    assert (np.abs(fused).max(axis=1) > 0).all()
+
+
+def test_ffn_combine_k1_rejects_layers_with_more_experts_per_token():
+    cfg = si.small_config("k2", T=64, d=64, E=4, k=2, F=64)
+    buf = layer.MoeBuffers(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, cfg.dtype, cfg.renorm)
+    z = torch.zeros((cfg.E, cfg.F, cfg.d), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.MoeError) as err:
+        B.moe_grouped_ffn_combine_k1(buf.shape, buf.y, buf.src_assign, buf.offsets, z, z, z, buf.topk_w,
+                                     buf.h, buf.y)
+    assert err.value.code == -2
