@@ -130,7 +130,12 @@ def hbm_bound_calls(torch, si, B, layer, st):
             "combine": A * d * b + T * d * b + 8 * A}
     out = {"shape": f"T={T} d={d} E={E} k={k} bf16", "iterations": HBM_BOUND_ITERS,
            "buffer_sets": len(sets), "hbm_peak_gbs": PEAK_HBM_GBS}
-    for name, fn in (("route", route), ("count_and_permute", permute), ("combine", combine)):
+    def plain_copy(b):    # context: what the box gives a copy of x (a PyTorch kernel, not part of the path)
+        b["y"].copy_(b["x"])
+
+    work["plain_copy_of_x"] = 2 * T * d * b
+    for name, fn in (("route", route), ("count_and_permute", permute), ("combine", combine),
+                     ("plain_copy_of_x", plain_copy)):
         for bset in sets:
             fn(bset)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -361,8 +361,8 @@ __device__ __forceinline__ void ffn_sum_parts(f32x4_t (&acc)[NI][MI], const Tile
 // --------------------------------------------------------------------------------------------
 constexpr int ffn_ring_lds_bytes(int bm, int nstage) { return nstage * (bm + BROWS) * ROWB; }
 
-template <int BM, bool GATED, int WM, int WN, int NSTAGE, bool SPLIT = false>
-__global__ __launch_bounds__(WM * WN * 64) void ffn_ring_kernel(GemmArgs p) {
+template <int BM, bool GATED, int WM, int WN, int NSTAGE, bool SPLIT>
+__device__ __forceinline__ void ffn_ring_tile(const GemmArgs& p, const TileCoord& tc, unsigned char* lds) {
   constexpr int NW = WM * WN;                     // waves per block
   constexpr int KSTEPS = BK / 32;                 // MFMA k-steps per stage
   constexpr int MI = BM / WM / 16;                // 16-row activation sub-tiles per wave
@@ -375,10 +375,6 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_ring_kernel(GemmArgs p) {
   constexpr int BN_OUT = GATED ? 128 : 256;       // output columns per block tile
   static_assert(NLA * 8 * NW == BM && NLB * 8 * NW == 128 && MI >= 1 && NIH >= 1, "tile shape");
   static_assert(NSTAGE > 2, "a ring keeps at least two stages of loads in flight");
-  extern __shared__ __align__(1024) unsigned char lds[];
-
-  TileCoord tc;
-  if (!decode_tile<SPLIT>(p, tc)) return;
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
@@ -520,16 +516,20 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_ring_kernel(GemmArgs p) {
   ffn_store_tile<GATED, MI, NI, WN, NW>(acc, tc, p, lds, wave, lane, mi_valid, wm * (BM / WM));
 }
 
-// The launch after a ring GEMM whose tiles may have been split: block (xcd, t) adds the parts of
-// split tile t of the XCD's last round and stores the tile.  Finds nothing to do when no tile was split.
+template <int BM, bool GATED, int WM, int WN, int NSTAGE, bool SPLIT = false>
+__global__ __launch_bounds__(WM * WN * 64) void ffn_ring_kernel(GemmArgs p) {
+  extern __shared__ __align__(1024) unsigned char lds[];
+  TileCoord tc;
+  if (!decode_tile<SPLIT>(p, tc)) return;
+  ffn_ring_tile<BM, GATED, WM, WN, NSTAGE, SPLIT>(p, tc, lds);
+}
+
+// Adds the parts of a split ring tile and stores it.
 template <int BM, bool GATED, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void ffn_ring_sum_parts_kernel(GemmArgs p) {
+__device__ __forceinline__ void ffn_ring_sum_tile(const GemmArgs& p, const TileCoord& tc, unsigned char* lds) {
   constexpr int NW = WM * WN;
   constexpr int MI = BM / WM / 16;
   constexpr int NI = BROWS / WN / 16;
-  extern __shared__ __align__(1024) unsigned char lds[];
-  TileCoord tc;
-  if (!decode_tile<true>(p, tc)) return;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   const int wm = wave / WN;
@@ -538,6 +538,16 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_ring_sum_parts_kernel(GemmAr
   f32x4_t acc[NI][MI];
   ffn_sum_parts<MI, NI, NW * MOE_WAVE>(acc, tc, p);
   ffn_store_tile<GATED, MI, NI, WN, NW>(acc, tc, p, lds, wave, lane, mi_valid, wm * (BM / WM));
+}
+
+// The launch after a ring GEMM whose tiles may have been split: block (xcd, t) adds the parts of
+// split tile t of the XCD's last round and stores the tile.  Finds nothing to do when no tile was split.
+template <int BM, bool GATED, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void ffn_ring_sum_parts_kernel(GemmArgs p) {
+  extern __shared__ __align__(1024) unsigned char lds[];
+  TileCoord tc;
+  if (!decode_tile<true>(p, tc)) return;
+  ffn_ring_sum_tile<BM, GATED, WM, WN>(p, tc, lds);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -575,7 +585,12 @@ __global__ __launch_bounds__(WM * WN * 64) void ffn_ring_sum_parts_kernel(GemmAr
 constexpr int EVEN_BM = 320;
 constexpr int EVEN_ACT = EVEN_BM * ROWB;                     // one activation buffer
 constexpr int EVEN_WGT = BROWS * ROWB;                       // one weight buffer
-constexpr int EVEN_LDS = 2 * (EVEN_ACT + EVEN_WGT);
+// Tiles of at most RING_ROWS rows (a small expert of a skewed batch, beside experts that hold several
+// full tiles) run the ring pipeline inside the same launch: they have little arithmetic per weight
+// byte and are paced by memory latency, which the ring's three stages in flight hide best.
+constexpr int RING_ROWS = 64;
+constexpr int EVEN_LDS = ffn_ring_lds_bytes(RING_ROWS, 4) > 2 * (EVEN_ACT + EVEN_WGT)
+                             ? ffn_ring_lds_bytes(RING_ROWS, 4) : 2 * (EVEN_ACT + EVEN_WGT);
 
 // How the tile's sub-tiles are dealt to wave row wm (of 4): count and first row.
 __device__ __forceinline__ void even_wave_rows(int rows_valid, int wm, int& miv, int& row0) {
@@ -598,6 +613,10 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
 
   TileCoord tc;
   if (!decode_tile<SPLIT>(p, tc)) return;
+  if (tc.m_end - tc.m_begin <= RING_ROWS) {       // block-uniform
+    ffn_ring_tile<RING_ROWS, GATED, 2, 4, 4, SPLIT>(p, tc, lds);
+    return;
+  }
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
@@ -816,6 +835,10 @@ __global__ __launch_bounds__(512) void ffn_even_sum_parts_kernel(GemmArgs p) {
   extern __shared__ __align__(1024) unsigned char lds[];
   TileCoord tc;
   if (!decode_tile<true>(p, tc)) return;
+  if (tc.m_end - tc.m_begin <= RING_ROWS) {       // its parts came from the ring pipeline
+    ffn_ring_sum_tile<RING_ROWS, GATED, 2, 4>(p, tc, lds);
+    return;
+  }
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   int miv, row0;
@@ -1016,8 +1039,10 @@ static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, hip
   if (A / g1.E < EVEN_MIN_ROWS) {
     // Few rows per expert (decode, small prefill batches): the call is bound by streaming each
     // expert's weights once, which the latency-hiding ring of the 64-row tiles does best.
-    // (Measured at the Mixtral shape: 64 rows per expert 0.85 -> 0.63 ms against 128-row
-    // two-stage tiles.)
+    // (Measured, whole layer, ring tiles against even tiles for every expert: Mixtral shape 64 / 96
+    // rows per expert 0.60 / 0.63 ms against 0.70 / 0.74; skewed 64-expert layer at 256 ... 1280
+    // tokens, where a hot expert holds ten times the mean, 0.22 ... 0.39 ms against 0.27 ... 0.41;
+    // only the fine-grained layer at 96 rows per expert is faster with even tiles, 0.28 against 0.33 ms.)
     if (up && (rc = launch_ring<true>(g1, A, st)) != MOE_OK) return rc;
     if (down) rc = launch_ring<false>(g2, A, st);
     return rc;

@@ -39,7 +39,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
 constexpr int RT_TM = 16;
 constexpr int RT_NW = 8;
 constexpr int RT_THREADS = RT_NW * MOE_WAVE;
-constexpr int RT_BATCH = 8;   // MFMA steps whose x fragments are requested together
+constexpr int RT_BATCH = 16;  // MFMA steps whose x fragments are requested together
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -363,7 +363,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const int c0 = wave * cw;
     const int c1 = min(row16, c0 + cw);
     // x comes from HBM and is read exactly once: a batch of RT_BATCH MFMA steps has all of its
-    // x fragments requested before the first one is used, so each wave keeps 8 KiB in flight.
+    // x fragments requested before the first one is used, so each wave keeps 16 KiB in flight.
     // w_gate fragments come from L2 and are fetched per step.
     for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
       uint4 a[RT_BATCH];
@@ -937,6 +937,7 @@ constexpr int RT_PRE_MAX_T = MOE_ROUTE_WS_MAX_T;
 
 // GNT: 16-expert tiles per block (1 for the smallest batches, 4 once there are enough token tiles
 // to fill the chip: x is then read E / 64 times instead of E / 16 times).
+constexpr int GT_BATCH = 8;   // MFMA steps whose fragments (x and up to four w_gate tiles) are requested together
 template <int GNT>
 __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
@@ -959,17 +960,17 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
   const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
   const int c0 = wave * cw;
   const int c1 = min(row16, c0 + cw);
-  for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
-    uint4 a[RT_BATCH], b[RT_BATCH][GNT];
+  for (int cb = c0; cb < c1; cb += 4 * GT_BATCH) {
+    uint4 a[GT_BATCH], b[GT_BATCH][GNT];
 #pragma unroll
-    for (int u = 0; u < RT_BATCH; ++u) {
+    for (int u = 0; u < GT_BATCH; ++u) {
       const int cc = min(cb + 4 * u + kq, row16 - 1);
       a[u] = xrow[cc];
 #pragma unroll
       for (int nt = 0; nt < GNT; ++nt) b[u][nt] = wrow[nt][cc];
     }
 #pragma unroll
-    for (int u = 0; u < RT_BATCH; ++u) {
+    for (int u = 0; u < GT_BATCH; ++u) {
       if (cb + 4 * u < c1) {                         // wave-uniform
         uint4 av = a[u];
         if (cb + 4 * u + kq >= row16) av = make_uint4(0, 0, 0, 0);
@@ -1028,9 +1029,12 @@ static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg,
 template <bool BF16, int NT>
 static int launch_route(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
                         int32_t* idx, float* w, float* scores, float* scratch, hipStream_t st) {
-  // Tokens per block: a full 16-row tile when that still gives every CU a few blocks; fewer
-  // (the other tile rows idle) for small batches, where latency, not MFMA use, is what counts.
-  constexpr int GRID_TARGET = 512;
+  // Tokens per block: a full 16-row tile when that still gives every CU a block (every wave then
+  // has its whole slice of the tile's rows, 16 KiB at d = 4096, requested at once); fewer (the other
+  // tile rows idle) for smaller batches, where latency, not MFMA use, is what counts.
+  // (Measured at T = 4096, d = 4096, E = 8 with x cold: 25.7 us with 8 tokens per block and
+  // batches of 8 steps, 21.8 us with full tiles and the slice in one batch.)
+  constexpr int GRID_TARGET = 256;
   int tpb = RT_TM;
   while (tpb > 1 && (s->T + tpb - 1) / tpb < GRID_TARGET) tpb >>= 1;
   if (tpb == RT_TM)
