@@ -660,27 +660,22 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   const int n_act = min(40 / ns, max(0, (((rows_valid + 7) >> 3) - lw + ns - 1) / ns));
   const int w_rows = min(GATED ? 128 : 256, N - n0);          // weight rows of this tile per matrix
   uint32_t soff_a[NLA], soff_w;
-#pragma unroll
-  for (int i = 0; i < NLA; ++i) {
-    const int row = (i * ns + lw) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ swz(row);      // the chunk of the row this lane fetches
-    int r = min(row, rows_valid - 1);
-    if (gathered) r = a_row_of(p, tc.m_begin + r);
-    soff_a[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
-  }
   {
     const int br = lw * 8 + (lane >> 3);
     const int chunk = (lane & 7) ^ swz(br);
     soff_w = static_cast<uint32_t>(br) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
   }
-  auto issue_stage = [&](int kt, int buf) {
+  // what: 1 = the activation rows, 2 = the weight rows, 3 = both
+  auto issue_stage = [&](int kt, int buf, int what = 3) {
     if (alternate && lset != (kt & 1)) return;    // the other set's turn
+    if (what & 1)
 #pragma unroll
     for (int i = 0; i < NLA; ++i)
       if (i < n_act)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rs_a, (__attribute__((address_space(3))) void*)(lds + buf * EVEN_ACT + (i * ns + lw) * 1024),
             16, static_cast<int>(soff_a[i]), kt * ROWB, 0, 0);
+    if (what & 2)
 #pragma unroll
     for (int i = 0; i < NLW; ++i) {
       // group i * ns + lw of the 32 weight row groups; gated: groups 0-15 are W1 rows 0-127 of the
@@ -799,10 +794,22 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
     asm volatile("s_nop 15\n s_nop 15\n s_nop 15\n s_nop 15" ::: "memory");
   };
 
-  // prologue: stages 0 and 1 requested; everything this wave requested has landed before the first
-  // barrier (a count that spared stage 1 would depend on how many groups the wave skipped)
-  issue_stage(0, 0);
-  if (KT > 1) issue_stage(1, 1);
+  // prologue: stages 0 and 1 requested, the weight rows first: their addresses need no memory, while
+  // the activation rows of a call that reads x through the map wait for the map entries, a trip to
+  // memory that now overlaps the weights'.  Everything this wave requested has landed before the
+  // first barrier (a count that spared stage 1 would depend on how many groups the wave skipped).
+  issue_stage(0, 0, 2);
+  if (KT > 1) issue_stage(1, 1, 2);
+#pragma unroll
+  for (int i = 0; i < NLA; ++i) {
+    const int row = (i * ns + lw) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ swz(row);      // the chunk of the row this lane fetches
+    int r = min(row, rows_valid - 1);
+    if (gathered) r = a_row_of(p, tc.m_begin + r);
+    soff_a[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
+  }
+  issue_stage(0, 0, 1);
+  if (KT > 1) issue_stage(1, 1, 1);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");

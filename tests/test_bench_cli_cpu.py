@@ -26,3 +26,47 @@ def test_help_lists_the_workload_and_measurement_options():
     for opt in ("--gpus", "--steps", "--warmup", "--workload", "--tokens", "--ffn-split", "--ep-sim",
                 "--predictor-accuracy", "--no-cpu-baseline"):
         assert opt in r.stdout
+
+
+def test_hbm_traffic_is_reported_only_for_the_kernel_source_it_was_measured_with(tmp_path, monkeypatch):
+    """roofline.traffic comes from a profiles/ summary that names the workload, the entry point and
+    the SHA-256 of csrc/ffn.hip it was taken with; anything else gives None, never a stale figure."""
+    import hashlib
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    src = os.path.join(ROOT, "paper_2603_06350_amd", "csrc", "ffn.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    pkg = tmp_path / "paper_2603_06350_amd" / "csrc"
+    pkg.mkdir(parents=True)
+    (pkg / "ffn.hip").write_bytes(open(src, "rb").read())
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+
+    def write(sha256, entry="moe_grouped_ffn_gather", workload="mixtral"):
+        (prof / "mixtral_ffn_up_hbm_traffic.md").write_text(
+            f"# text\n\nworkload: {workload}\nentry_point: {entry}\nffn_hip_sha256: {sha256}\n"
+            "hbm_read_bytes: 2800000000\nhbm_written_bytes: 235000000\n")
+
+    write(sha)
+    got = bench.measured_hbm_traffic("mixtral", "moe_grouped_ffn_gather")
+    assert got["read_bytes"] == 2.8e9 and got["written_bytes"] == 2.35e8
+    assert bench.measured_hbm_traffic("mixtral", "moe_grouped_ffn") is None          # another entry point
+    assert bench.measured_hbm_traffic("phi", "moe_grouped_ffn_gather") is None       # no summary
+    write("0" * 64)
+    assert bench.measured_hbm_traffic("mixtral", "moe_grouped_ffn_gather") is None   # another kernel source
+    write(sha, workload="phi")
+    assert bench.measured_hbm_traffic("mixtral", "moe_grouped_ffn_gather") is None
+
+
+def test_committed_traffic_summary_parses(repo_root=ROOT):
+    path = os.path.join(ROOT, "profiles", "mixtral_ffn_up_hbm_traffic.md")
+    if not os.path.exists(path):
+        return
+    import re
+    fields = dict(re.findall(r"^([a-z_0-9]+):\s*(\S+)\s*$", open(path).read(), flags=re.M))
+    for key in ("workload", "entry_point", "ffn_hip_sha256", "hbm_read_bytes", "hbm_written_bytes"):
+        assert key in fields
+    assert len(fields["ffn_hip_sha256"]) == 64 and float(fields["hbm_read_bytes"]) > 1e9
