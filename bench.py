@@ -87,6 +87,80 @@ def measured_hbm_traffic(cfg_name, entry_point):
             "source": os.path.relpath(path, ROOT)}
 
 
+def achievable_peaks():
+    """What the box itself sustains on the two rooflines, from the stand-alone micro-benchmarks under
+    csrc/microbench, each run in a fresh child process after the timed region: back-to-back
+    independent v_mfma_f32_16x16x32_bf16 on random operands held in registers (no memory traffic),
+    a read-only stream over 4 GiB of HBM, and the up-projection's operand tiles streamed L2 -> LDS
+    with no arithmetic.  Context for the published peaks the roofline fractions are priced against;
+    None for a program that is not built."""
+    import re
+    import subprocess
+    mb = os.path.join(ROOT, "paper_2603_06350_amd", "csrc", "microbench")
+
+    def run(name, unit, pick):
+        exe = os.path.join(mb, name + ".exe")
+        if not os.path.exists(exe):
+            return None
+        try:
+            txt = subprocess.run([exe], capture_output=True, text=True, timeout=120).stdout
+        except (OSError, subprocess.TimeoutExpired):
+            return None
+        vals = [float(m.group(1)) for line in txt.splitlines() if pick in line
+                for m in [re.search(r"([0-9.]+) " + unit, line)] if m]
+        return max(vals) if vals else None
+
+    mfma = run("mfma_rate", "TFLOP/s", "16x16x32")
+    hbm = run("hbm_read_stream", "TB/s", "contiguous")
+    l2 = run("l2_to_lds_stream", "TB/s", "buffer_load")
+    return {"mfma_bf16_16x16x32_tflops": mfma,
+            "mfma_frac_of_published_peak": None if mfma is None else mfma / PEAK_BF16_MFMA_TFLOPS,
+            "hbm_read_stream_gbs": None if hbm is None else hbm * 1e3,
+            "hbm_frac_of_published_peak": None if hbm is None else hbm * 1e3 / PEAK_HBM_GBS,
+            "l2_to_lds_operand_stream_gbs": None if l2 is None else l2 * 1e3,
+            "source": "paper_2603_06350_amd/csrc/microbench/{mfma_rate,hbm_read_stream,l2_to_lds_stream}.exe, "
+                      "best line of each, child processes after the timed region"}
+
+
+def vendor_dense_gemm(torch, cfg, x, w1, w2):
+    """Context, not part of the path: the vendor library's dense GEMM (torch.matmul, hipBLASLt on
+    ROCm) on the dense equivalents of the two projections (all A = T*k rows against one expert's
+    [W1;W3] and W2, the same flops as the grouped calls) with operands of the workload's own value
+    distributions (the figure depends on them: all-zero operands run about a third faster on this
+    chip), and the same contractions on all-zero operands.  After the timed region."""
+    A = cfg.T * cfg.k
+    rows = x[torch.arange(A, device="cuda") % cfg.T]
+    w13 = torch.cat([w1[0], w1[0]], dim=0)            # [2F, d]
+    h = torch.randn((A, cfg.F), device="cuda", dtype=torch.float32).mul_(0.5).to(rows.dtype)
+    out = {}
+    for name, a, b in (("up", rows, w13), ("down", h, w2[0])):
+        for kind in ("workload_values", "zeros"):
+            aa, bb = (a, b) if kind == "workload_values" else (torch.zeros_like(a), torch.zeros_like(b))
+            f = lambda: torch.matmul(aa, bb.t())
+            for _ in range(3):
+                f()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(10):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 10
+            out[f"{name}_{kind}_tflops"] = 2.0 * aa.shape[0] * bb.shape[0] * aa.shape[1] / (ms * 1e-3) / 1e12
+    out["shapes"] = f"up [{A} x {cfg.d}] x [{cfg.d} x {2 * cfg.F}], down [{A} x {cfg.F}] x [{cfg.F} x {cfg.d}]"
+    return out
+
+
+def calibration_copy(torch):
+    """One plain copy kernel of known size (1 GiB read + 1 GiB written) so that a profiler's HBM
+    byte counters can be scaled against a known quantity.  Outside every timed region."""
+    calib_src = torch.ones((512 << 20,), dtype=torch.bfloat16, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    torch.mul(calib_src, 1, out=calib_dst)
+    torch.cuda.synchronize()
+
+
 def hbm_bound_calls(torch, si, B, layer, st):
     """moe_route, moe_count_and_permute (with the row copy) and moe_combine at a bandwidth-bound
     batch: average time of HBM_BOUND_ITERS launches each (HIP events on the launch stream), two
@@ -175,6 +249,12 @@ def main():
                          "last round along K (moe_grouped_ffn_ws)")
     ap.add_argument("--no-hbm-bound", action="store_true",
                     help="skip the timings of route / count+permute / combine at the bandwidth-bound batch")
+    ap.add_argument("--hbm-bound-only", action="store_true",
+                    help="time only route / count+permute / combine at the bandwidth-bound batch and "
+                         "print that object (for a profile of those kernels alone)")
+    ap.add_argument("--no-achievable-peaks", action="store_true",
+                    help="skip the micro-benchmarks that measure what the box sustains on MFMA and HBM, "
+                         "and the vendor library's dense GEMM on the same flops")
     ap.add_argument("--no-consumers", action="store_true",
                     help="skip the timings of the load-statistic consumers (scaler, predictor)")
     args = ap.parse_args()
@@ -192,6 +272,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     B.load()
+    if args.hbm_bound_only:
+        calibration_copy(torch)
+        print(json.dumps({"hbm_bound_calls": hbm_bound_calls(torch, si, B, layer, torch.cuda.current_stream())}))
+        return
     cfg = si.CONFIGS[args.workload]
     if args.tokens > 0 and args.tokens != cfg.T:
         import dataclasses
@@ -277,13 +361,7 @@ def main():
         for fn in make_calls(fused):
             fn()
 
-    # One plain copy kernel of known size (1 GiB read + 1 GiB written) so that a profiler's
-    # HBM byte counters can be scaled against a known quantity.  Outside the timed region.
-    calib_src = torch.ones((512 << 20,), dtype=torch.bfloat16, device="cuda")
-    calib_dst = torch.empty_like(calib_src)
-    torch.mul(calib_src, 1, out=calib_dst)
-    torch.cuda.synchronize()
-    del calib_src, calib_dst
+    calibration_copy(torch)
 
     ms_per_step, calls = time_form(fused, args.warmup, args.steps)
     per_call_ms, per_call_ms_min, per_call_ms_median = calls["avg"], calls["min"], calls["median"]
@@ -450,6 +528,11 @@ def main():
         B.moe_count_and_permute(sh, x, buf.topk_idx, buf.counts, buf.offsets, buf.dst_row,
                                 buf.src_assign, buf.x_perm, buf.workspace, buf.ws_bytes, st)
         out["ep_simulation"] = ep_sim.simulate(buf, x, w1, w3, w2, args.ep_sim)
+    if not args.no_achievable_peaks:
+        torch.cuda.synchronize()
+        roofline["achievable_peak"] = achievable_peaks()
+        if cfg.dtype == si.BF16:
+            roofline["vendor_dense_gemm"] = vendor_dense_gemm(torch, cfg, x, w1, w2)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, L, cfg.T)
     print(json.dumps(out))

@@ -600,23 +600,24 @@ __device__ __forceinline__ void even_wave_rows(int rows_valid, int wm, int& miv,
   row0 = 16 * (wm * q + min(wm, r));
 }
 
-template <bool GATED, bool SPLIT, bool ALTERNATE>
-__global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
+// MI: 16-row sub-tiles a wave can hold.  MI = 5: tiles of up to 320 rows, two activation and two weight
+// buffers (144 KiB).  MI = 4: tiles of up to 256 rows; the 16 KiB the activation buffers give back
+// make a third weight buffer (160 KiB), and the weight rows are requested a stage earlier than the
+// activation rows: they are the operand that misses the L2 (an XCD's tiles share activation
+// rows far more often than weight rows), so their requests take longest to return.
+template <bool GATED, bool SPLIT, bool ALTERNATE, int MI>
+__device__ __forceinline__ void ffn_even_tile(const GemmArgs& p, const TileCoord& tc, unsigned char* lds) {
   constexpr int NW = 8, WN = 2;
-  constexpr int BM = EVEN_BM, MI = 5, NI = 8;
+  constexpr int BM = MI * 64, NI = 8;
   constexpr int NIH = GATED ? NI / 2 : NI;
   constexpr int NLA = BM / 8 / 4;                 // up to 10 activation row groups per loading wave and stage
   constexpr int NLW = BROWS / 8 / 4;              // up to 8 weight row groups
   constexpr int BN_OUT = GATED ? 128 : 256;
-  constexpr int W_BASE = 2 * EVEN_ACT;            // LDS offset of the weight buffers
-  extern __shared__ __align__(1024) unsigned char lds[];
-
-  TileCoord tc;
-  if (!decode_tile<SPLIT>(p, tc)) return;
-  if (tc.m_end - tc.m_begin <= RING_ROWS) {       // block-uniform
-    ffn_ring_tile<RING_ROWS, GATED, 2, 4, 4, SPLIT>(p, tc, lds);
-    return;
-  }
+  constexpr int ACT = BM * ROWB;                  // one activation buffer
+  constexpr int NWB = MI == 4 ? 3 : 2;            // weight buffers
+  constexpr int W_BASE = 2 * ACT;                 // LDS offset of the weight buffers
+  static_assert(MI == 4 || MI == 5, "wave tile");
+  static_assert(W_BASE + NWB * EVEN_WGT <= EVEN_LDS, "LDS budget");
 
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
@@ -657,7 +658,7 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
       const_cast<bf16_t*>(B0 + static_cast<int64_t>(n0) * K), 0, 0x7FFFFFFF, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(B1 + static_cast<int64_t>(n0) * K), 0, 0x7FFFFFFF, 0x00020000);
-  const int n_act = min(40 / ns, max(0, (((rows_valid + 7) >> 3) - lw + ns - 1) / ns));
+  const int n_act = min(BM / 8 / ns, max(0, (((rows_valid + 7) >> 3) - lw + ns - 1) / ns));
   const int w_rows = min(GATED ? 128 : 256, N - n0);          // weight rows of this tile per matrix
   uint32_t soff_a[NLA], soff_w;
   {
@@ -665,33 +666,41 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
     const int chunk = (lane & 7) ^ swz(br);
     soff_w = static_cast<uint32_t>(br) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
   }
-  // what: 1 = the activation rows, 2 = the weight rows, 3 = both
-  auto issue_stage = [&](int kt, int buf, int what = 3) {
-    if (alternate && lset != (kt & 1)) return;    // the other set's turn
-    if (what & 1)
+  // The activation rows of stage kt go to activation buffer kt % 2 and are requested two stages
+  // ahead, the weight rows to weight buffer kt % NWB, NWB stages ahead.  With ALTERNATE the requests
+  // made after the barrier of stage j (activations of j + 2, weights of j + NWB) all come from
+  // wave set j & 1.
+  auto issue_act = [&](int kt) {
+    if (alternate && lset != (kt & 1)) return;
 #pragma unroll
     for (int i = 0; i < NLA; ++i)
       if (i < n_act)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rs_a, (__attribute__((address_space(3))) void*)(lds + buf * EVEN_ACT + (i * ns + lw) * 1024),
+            rs_a, (__attribute__((address_space(3))) void*)(lds + (kt & 1) * ACT + (i * ns + lw) * 1024),
             16, static_cast<int>(soff_a[i]), kt * ROWB, 0, 0);
-    if (what & 2)
+  };
+  // Every wave makes the same number of weight requests per stage (W_LOADS), so that a wait can
+  // leave exactly one stage's weight requests outstanding: a group outside the weight matrix (the
+  // last n-tile of a matrix whose row count is not a multiple of the tile) re-reads the tile's
+  // first rows; its products are never stored.
+  constexpr int W_LOADS = 32 / ns;
+  auto issue_wgt = [&](int kt, int wb) {
+    if (alternate && lset != ((kt + NWB) & 1)) return;
 #pragma unroll
-    for (int i = 0; i < NLW; ++i) {
+    for (int i = 0; i < W_LOADS; ++i) {
       // group i * ns + lw of the 32 weight row groups; gated: groups 0-15 are W1 rows 0-127 of the
       // tile, groups 16-31 the same rows of W3
       const int g0 = i * ns * 8;                  // first row of the step (lw = 0)
-      const int jr = GATED ? (g0 & 127) : g0;     // ... inside its matrix
-      if (g0 < 256 && jr < w_rows) {
-        if (!GATED || g0 < 128)
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              rs_b0, (__attribute__((address_space(3))) void*)(lds + W_BASE + buf * EVEN_WGT + (i * ns + lw) * 1024),
-              16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
-        else
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(
-              rs_b1, (__attribute__((address_space(3))) void*)(lds + W_BASE + buf * EVEN_WGT + (i * ns + lw) * 1024),
-              16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
-      }
+      int jr = GATED ? (g0 & 127) : g0;           // ... inside its matrix
+      if (jr >= w_rows) jr = 0;
+      if (!GATED || g0 < 128)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rs_b0, (__attribute__((address_space(3))) void*)(lds + W_BASE + wb * EVEN_WGT + (i * ns + lw) * 1024),
+            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rs_b1, (__attribute__((address_space(3))) void*)(lds + W_BASE + wb * EVEN_WGT + (i * ns + lw) * 1024),
+            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
     }
   };
 
@@ -723,10 +732,9 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "i"(off) : "memory")
 #define MOE_MFMA(c, w, x) \
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(w), "v"(x))
-#define MOE_X_OFF(buf, mi) ((buf) * EVEN_ACT + (mi) * 16 * ROWB)
-#define MOE_W_OFF(buf, ni) \
-  ((buf) * EVEN_WGT + (GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
-  static_assert(MOE_W_OFF(1, NI - 1) < 65536 && MOE_X_OFF(1, MI - 1) < 65536, "ds_read offset field");
+#define MOE_X_OFF(buf, mi) ((buf) * ACT + (mi) * 16 * ROWB)
+#define MOE_W_OFF(ni) ((GATED ? ((ni) / NIH) * 128 + ((ni) % NIH) * 16 : (ni) * 16) * ROWB)
+  static_assert(MOE_W_OFF(NI - 1) < 65536 && MOE_X_OFF(1, MI - 1) < 65536, "ds_read offset field");
 
   auto k_loop = [&](auto miv_c) {
     constexpr int MIV = decltype(miv_c)::value;
@@ -743,8 +751,9 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
         }
       }
     };
-    // kk, buf: the k-step and buffer the next fragments come from
-    auto part2 = [&](auto kk_c, auto buf_c) {
+    // kk, buf: the k-step and activation buffer the next fragments come from; wv: this lane's
+    // address in the weight buffer they come from
+    auto part2 = [&](auto kk_c, auto buf_c, int wv) {
       constexpr int KK = decltype(kk_c)::value, BUF = decltype(buf_c)::value;
       if constexpr (MIV > 0) {
 #pragma unroll
@@ -754,7 +763,7 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
         for (int ni = 0; ni < NI; ++ni) {
 #pragma unroll
           for (int mi = P1; mi < MIV; ++mi) MOE_MFMA(acc[ni][mi], w[ni], x[mi]);
-          MOE_RD(w[ni], wa[KK], MOE_W_OFF(BUF, ni));
+          MOE_RD(w[ni], wv, MOE_W_OFF(ni));
         }
 #pragma unroll
         for (int mi = P1; mi < MIV; ++mi) MOE_RD(x[mi], xa[KK], MOE_X_OFF(BUF, mi));
@@ -762,23 +771,33 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
     };
     using K0 = std::integral_constant<int, 0>;
     using K1 = std::integral_constant<int, 1>;
+    int wb = 0;                                   // weight buffer of the current stage (uniform)
     auto stage = [&](int kt, auto par_c) {
       constexpr int PAR = decltype(par_c)::value;
+      const int wb_next = wb + 1 == NWB ? 0 : wb + 1;
       part1();
-      part2(K1{}, std::integral_constant<int, PAR>{});
+      part2(K1{}, std::integral_constant<int, PAR>{}, wa[1] + wb * EVEN_WGT);
       part1();
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      // Stage kt + 1 must have landed.  Requests return in order, and the last ones this wave made
+      // (after the barrier of stage kt - 1, if it was its turn) were the activation rows of kt + 1,
+      // then, with three weight buffers, the weight rows of kt + 2: those may stay in flight.
+      if (NWB == 3 && kt >= 1 && kt + 2 < KT && (!alternate || lset == ((kt - 1) & 1)))
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"i"(W_LOADS) : "memory");
+      else
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       asm volatile("" ::: "memory");
-      if (kt + 2 < KT) issue_stage(kt + 2, PAR);
+      if (kt + 2 < KT) issue_act(kt + 2);
+      if (kt + NWB < KT) issue_wgt(kt + NWB, wb);
       // (after the tile's last stage these reads return whatever the buffer holds and go unused)
-      part2(K0{}, std::integral_constant<int, PAR ^ 1>{});
+      part2(K0{}, std::integral_constant<int, PAR ^ 1>{}, wa[0] + wb_next * EVEN_WGT);
+      wb = wb_next;
     };
     if constexpr (MIV > 0) {
 #pragma unroll
       for (int mi = 0; mi < P1; ++mi) MOE_RD(x[mi], xa[0], MOE_X_OFF(0, mi));
 #pragma unroll
-      for (int ni = 0; ni < NI; ++ni) MOE_RD(w[ni], wa[0], MOE_W_OFF(0, ni));
+      for (int ni = 0; ni < NI; ++ni) MOE_RD(w[ni], wa[0], MOE_W_OFF(ni));
 #pragma unroll
       for (int mi = P1; mi < MIV; ++mi) MOE_RD(x[mi], xa[0], MOE_X_OFF(0, mi));
     }
@@ -798,8 +817,9 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   // the activation rows of a call that reads x through the map wait for the map entries, a trip to
   // memory that now overlaps the weights'.  Everything this wave requested has landed before the
   // first barrier (a count that spared stage 1 would depend on how many groups the wave skipped).
-  issue_stage(0, 0, 2);
-  if (KT > 1) issue_stage(1, 1, 2);
+#pragma unroll
+  for (int s = 0; s < NWB; ++s)
+    if (s < KT) issue_wgt(s, s);
 #pragma unroll
   for (int i = 0; i < NLA; ++i) {
     const int row = (i * ns + lw) * 8 + (lane >> 3);
@@ -808,8 +828,8 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
     if (gathered) r = a_row_of(p, tc.m_begin + r);
     soff_a[i] = static_cast<uint32_t>(r) * static_cast<uint32_t>(K) * 2u + static_cast<uint32_t>(chunk) * 16u;
   }
-  issue_stage(0, 0, 1);
-  if (KT > 1) issue_stage(1, 1, 1);
+  issue_act(0);
+  if (KT > 1) issue_act(1);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -819,7 +839,9 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
     case 2: k_loop(std::integral_constant<int, 2>{}); break;
     case 3: k_loop(std::integral_constant<int, 3>{}); break;
     case 4: k_loop(std::integral_constant<int, 4>{}); break;
-    default: k_loop(std::integral_constant<int, 5>{}); break;
+    default:
+      if constexpr (MI >= 5) k_loop(std::integral_constant<int, 5>{});
+      break;
   }
 #undef MOE_RD
 #undef MOE_MFMA
@@ -835,24 +857,50 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   ffn_store_tile<GATED, MI, NI, WN, NW>(acc, tc, p, lds, wave, lane, miv, row0);
 }
 
-// The launch after ffn_even_kernel<.., SPLIT>: adds the parts of every split tile and stores it.
-template <bool GATED>
-__global__ __launch_bounds__(512) void ffn_even_sum_parts_kernel(GemmArgs p) {
-  constexpr int NW = 8, WN = 2, MI = 5, NI = 8;
+// Tiles of at most this many rows of the down-projection take the form with three weight buffers.
+// (Measured on uniform batches at the Mixtral shape, 768 and 1024 rows per expert: the
+// down-projection, whose reduction is 14336 long, 11 % and 4.5 % faster; the up-projection, 4096
+// long, 1 % slower, so it keeps two weight buffers for every tile.)
+constexpr int EVEN_ROWS_3WB = 256;
+
+template <bool GATED, bool SPLIT, bool ALTERNATE>
+__global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   extern __shared__ __align__(1024) unsigned char lds[];
   TileCoord tc;
-  if (!decode_tile<true>(p, tc)) return;
-  if (tc.m_end - tc.m_begin <= RING_ROWS) {       // its parts came from the ring pipeline
-    ffn_ring_sum_tile<RING_ROWS, GATED, 2, 4>(p, tc, lds);
-    return;
-  }
+  if (!decode_tile<SPLIT>(p, tc)) return;
+  const int rows = tc.m_end - tc.m_begin;         // block-uniform
+  if (rows <= RING_ROWS)
+    ffn_ring_tile<RING_ROWS, GATED, 2, 4, 4, SPLIT>(p, tc, lds);
+  else if (!GATED && rows <= EVEN_ROWS_3WB)
+    ffn_even_tile<GATED, SPLIT, ALTERNATE, 4>(p, tc, lds);
+  else
+    ffn_even_tile<GATED, SPLIT, ALTERNATE, 5>(p, tc, lds);
+}
+
+// The launch after ffn_even_kernel<.., SPLIT>: adds the parts of every split tile and stores it.
+template <bool GATED, int MI>
+__device__ __forceinline__ void ffn_even_sum_tile(const GemmArgs& p, const TileCoord& tc, unsigned char* lds) {
+  constexpr int NW = 8, WN = 2, NI = 8;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / MOE_WAVE);
   int miv, row0;
-  even_wave_rows(min(tc.m_end - tc.m_begin, EVEN_BM), wave / WN, miv, row0);
+  even_wave_rows(min(tc.m_end - tc.m_begin, MI * 64), wave / WN, miv, row0);
   f32x4_t acc[NI][MI];
   ffn_sum_parts<MI, NI, NW * MOE_WAVE>(acc, tc, p);
   ffn_store_tile<GATED, MI, NI, WN, NW>(acc, tc, p, lds, wave, lane, miv, row0);
+}
+template <bool GATED>
+__global__ __launch_bounds__(512) void ffn_even_sum_parts_kernel(GemmArgs p) {
+  extern __shared__ __align__(1024) unsigned char lds[];
+  TileCoord tc;
+  if (!decode_tile<true>(p, tc)) return;
+  const int rows = tc.m_end - tc.m_begin;
+  if (rows <= RING_ROWS)                          // its parts came from the ring pipeline
+    ffn_ring_sum_tile<RING_ROWS, GATED, 2, 4>(p, tc, lds);
+  else if (!GATED && rows <= EVEN_ROWS_3WB)
+    ffn_even_sum_tile<GATED, 4>(p, tc, lds);
+  else
+    ffn_even_sum_tile<GATED, 5>(p, tc, lds);
 }
 
 // --------------------------------------------------------------------------------------------

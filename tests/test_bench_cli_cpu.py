@@ -70,3 +70,33 @@ def test_committed_traffic_summary_parses(repo_root=ROOT):
     for key in ("workload", "entry_point", "ffn_hip_sha256", "hbm_read_bytes", "hbm_written_bytes"):
         assert key in fields
     assert len(fields["ffn_hip_sha256"]) == 64 and float(fields["hbm_read_bytes"]) > 1e9
+
+
+def test_achievable_peaks_takes_the_best_matching_line_of_each_micro_benchmark(tmp_path, monkeypatch):
+    """roofline.achievable_peak parses the micro-benchmarks' own output lines: the best 16x16x32 MFMA
+    rate, the contiguous HBM stream, the buffer_load L2 -> LDS stream; a program that is not built
+    gives None, not a made-up figure."""
+    import importlib.util
+    import types
+    spec = importlib.util.spec_from_file_location("bench_under_test_peaks", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    mb = tmp_path / "paper_2603_06350_amd" / "csrc" / "microbench"
+    mb.mkdir(parents=True)
+    (mb / "mfma_rate.exe").write_text("")
+    (mb / "hbm_read_stream.exe").write_text("")
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    outputs = {
+        "mfma_rate.exe": "32x32x16 agpr acc, no barrier   waves/SIMD=2: 6.156 ms 2744 TFLOP/s\n"
+                         "16x16x32 vgpr acc, no barrier   waves/SIMD=1: 2.913 ms 1843 TFLOP/s\n"
+                         "16x16x32 vgpr acc, no barrier   waves/SIMD=2: 5.483 ms 1958 TFLOP/s\n",
+        "hbm_read_stream.exe": "contiguous, 4096 blocks x 256 threads        0.684 ms  6.28 TB/s\n"
+                               "packed stages, 2 stages in flight            0.685 ms  7.27 TB/s\n",
+    }
+    import subprocess as sp
+    monkeypatch.setattr(sp, "run", lambda cmd, **kw: types.SimpleNamespace(stdout=outputs[os.path.basename(cmd[0])]))
+    got = bench.achievable_peaks()
+    assert got["mfma_bf16_16x16x32_tflops"] == 1958.0
+    assert abs(got["mfma_frac_of_published_peak"] - 1958.0 / 2500.0) < 1e-12
+    assert got["hbm_read_stream_gbs"] == 6280.0
+    assert got["l2_to_lds_operand_stream_gbs"] is None
