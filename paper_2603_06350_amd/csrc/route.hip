@@ -1086,15 +1086,27 @@ static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, 
     constexpr int TILES_MAX = NT > 8 ? 4 : 8, TILES_MIN = NT > 4 ? 4 : 2;
     auto blocks = [&](int tiles) { return (s->T + 16 * tiles - 1) / (16 * tiles); };
     auto fits = [&](int tiles) { return s->d % (64 * (RT_NW / tiles)) == 0; };
-    // the most tiles per block that still give every CU a block ...
     int tiles = 0;
+    const int64_t gate_bytes = static_cast<int64_t>(s->E) * s->d * 2;
+    if (gate_bytes <= 128 * 1024) {
+      // A small gate matrix costs little to stream once per block: the fewest tiles per block that
+      // give every CU a block.  More, shorter blocks than the chip holds at once are in different
+      // phases (loading, selecting, storing), so the loads of one overlap the selection of another;
+      // with one resident wave of long blocks all load, then all select.  (Measured at d = 4096,
+      // E = 8: 65536 tokens 121 us with 8 tiles per block, 112 with 4, 102 with 2; 32768 tokens
+      // 70 -> 57 us; E = 16: 121 / 113 / 109 us.  At E = 16, d = 5120, where the matrix is 160 KB,
+      // and at E = 64 the order is the opposite: 127 / 135 / 141 us and 92 / 91 / 149 us.)
+      for (int c = TILES_MIN; c <= TILES_MAX && tiles == 0; c <<= 1)
+        if (blocks(c) >= 256 && fits(c)) tiles = c;
+    }
+    // otherwise the most tiles per block that still give every CU a block ...
     for (int c = TILES_MAX; c >= TILES_MIN && tiles == 0; c >>= 1)
       if (blocks(c) >= 256 && fits(c)) tiles = c;
-    // ... or, if the gate matrix is large (128 KB and more: the per-tile kernel streams all of it
-    // for every 16 tokens), the fewest tiles per block from 96 blocks on, from where this path
-    // measured faster than both other forms
-    if (tiles == 0 && static_cast<int64_t>(s->E) * s->d * 2 >= 128 * 1024 && blocks(TILES_MIN) >= 96 &&
-        fits(TILES_MIN))
+    // ... or the fewest tiles per block from 96 blocks on, from where this path measured faster than
+    // the per-tile kernel (which streams the whole gate matrix for every 16 tokens, and whose blocks
+    // all load, then all select): d = 4096, E = 8, 3072 / 4096 / 6144 tokens 17.6 / 14.2 / 25.1 us
+    // -> 13.1 / 13.4 / 14.6 us; E = 16 at 4096 tokens 21 -> 19 us
+    if (tiles == 0 && blocks(TILES_MIN) >= 96 && fits(TILES_MIN))
       tiles = TILES_MIN;
     if (tiles == 0) return false;
     if constexpr (NT <= 8) {
