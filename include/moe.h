@@ -73,21 +73,23 @@ int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes);
  * int32; topk_w [T,k] fp32; scores_out [T,E] fp32 or NULL (the scores the
  * choice was taken on).  The choice is taken on correctly rounded scores: a token
  * whose leading k+1 scores are not clearly separated after the fast fp32 gate
- * product is re-evaluated with fp64 sums.
+ * product (closer than 2^-19 |x_t| max_e |w_e|, a margin that follows the size of
+ * the terms that were added, not of their sum) is re-evaluated with fp64 sums.
  */
 int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,
               const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,
               void* hip_stream);
 
 /*
- * moe_route with a device workspace (same operation, same results).  For small
+ * moe_route with a device workspace (same operation: the same experts, weights
+ * and scores to the same tolerance).  For small
  * batches (T < 8192) with a large gate matrix the gate product is then spread over
  * the whole chip by a kernel of its own and the selection reads its scores from the
  * workspace; without a workspace (and without scores_out) every block has to pull
  * the whole gate matrix through one compute unit.  workspace: 16-byte aligned,
  * contents ignored on entry and undefined on return; moe_workspace_bytes() is
- * always enough.  If it is NULL, misaligned or smaller than T*E*4 bytes the call
- * behaves like moe_route (no error).
+ * always enough.  If it is NULL, misaligned or smaller than (T*E + T + E)*4 bytes
+ * ((T + E)*4 when scores_out is given) the call behaves like moe_route (no error).
  */
 int moe_route_ws(const moe_shape_t* shape, const void* x, const void* w_gate,
                  const float* gate_bias, int32_t* topk_idx, float* topk_w, float* scores_out,

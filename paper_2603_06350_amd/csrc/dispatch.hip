@@ -290,9 +290,10 @@ extern "C" int moe_workspace_bytes(const moe_shape_t* shape, size_t* out_bytes) 
   const int nth = moe::dispatch_threads(shape->E);
   const int64_t nb = (static_cast<int64_t>(shape->T) + nth - 1) / nth;
   size_t bytes = static_cast<size_t>(nb > 0 ? nb : 1) * shape->E * sizeof(int32_t);
-  // moe_route_ws keeps T x E fp32 scores between its two kernels for small batches
+  // moe_route_ws keeps T x E fp32 scores and T + E norms between its two kernels for small batches
   if (shape->T <= MOE_ROUTE_WS_MAX_T) {
-    const size_t route_bytes = static_cast<size_t>(shape->T) * shape->E * sizeof(float);
+    const size_t route_bytes =
+        (static_cast<size_t>(shape->T) * shape->E + shape->T + shape->E) * sizeof(float);
     if (route_bytes > bytes) bytes = route_bytes;
   }
   *out_bytes = (bytes + 255) & ~static_cast<size_t>(255);

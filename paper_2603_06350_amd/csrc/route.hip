@@ -20,7 +20,13 @@
 //
 // The integer choice must not depend on the order of an fp32 sum.  After the fast
 // pass a token is "ambiguous" if one of its k chosen scores has another score within
-// 2^-14 * max|logit| (plus a few ulps of the score itself).  For such tokens (about
+// 2^-19 * |x_t| * max_e |w_e| (Euclidean norms; plus a few ulps of the score itself).  The
+// rounding errors of the fast pass scale with the magnitude of the products and partial sums,
+// which the product of the norms bounds, not with the magnitude of the result: a token whose
+// large terms cancel has tiny logits and large errors.  Both norms come out of the same pass
+// (the diagonals of x x^T and w w^T tiles on the matrix cores).  For inputs without cancellation
+// the margin is about 2^-14 of the largest logit, some 60 times the fast pass's typical error.
+// For ambiguous tokens (about
 // 1% for 64 experts, ~0.03% for 8) the whole block re-scores the experts that could
 // still be among the first k (at most 16; all E if there are more) with exact
 // products and fp64 sums rounded once to fp32, which is the correctly rounded score
@@ -54,6 +60,21 @@ __device__ __forceinline__ float wave_max(float v) {
 
 constexpr int RT_CMAX = 16;   // candidate experts re-scored exactly for an ambiguous token
 
+// Two fast scores closer than RT_TOL * |x_t| * max_e |w_e| are re-scored exactly.
+constexpr float RT_TOL = 1.9073486328125e-06f;   // 2^-19
+
+// Element (i, i) of a 16 x 16 MFMA result tile (a lane holds column lane & 15, rows
+// 4 (lane >> 4) + v): held by the lanes with (lane & 15) >> 2 == lane >> 4, in component lane & 3.
+__device__ __forceinline__ bool rt_diag_lane(int lane) { return ((lane & 15) >> 2) == (lane >> 4); }
+__device__ __forceinline__ float rt_diag(const f32x4_t& a, int lane) {
+  const int v = lane & 3;
+  return v == 0 ? a[0] : (v == 1 ? a[1] : (v == 2 ? a[2] : a[3]));
+}
+__device__ __forceinline__ f32x4_t rt_mfma(uint4 a, uint4 b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                 __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
 // Largest value of a wave, on every lane: four DPP steps make each row of 16 lanes hold its
 // maximum (lane swaps inside quads, then the half-row and row mirrors), two row broadcasts carry
 // it across the four rows into lane 63.
@@ -79,11 +100,12 @@ __device__ __forceinline__ float wave_max_dpp(float v) {
 // pick costs a few dozen instructions whatever E is.  The extra round fetches the best score
 // that is NOT chosen: the picks come out in descending order, so a chosen score's nearest
 // neighbour is the pick before or after it.
+// bnd: |x_t| * max_e |w_e| of the token (see RT_TOL).
 // With `check`: if any of the k chosen experts has another score within the fast pass's error
 // margin, nothing is written; the experts that could still be among the first k are listed in
 // cand[] and their number is returned (RT_CMAX + 1 if there are too many).  Otherwise returns 0.
 template <int QE>
-__device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, int k, int renorm,
+__device__ int route_token(const float (&s)[QE], float bnd, bool check, int E, int k, int renorm,
                            int64_t t, int* __restrict__ cand, int32_t* __restrict__ topk_idx,
                            float* __restrict__ topk_w, float* __restrict__ scores_out) {
   const int lane = lane_id();
@@ -121,14 +143,14 @@ __device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, 
     if (i >= 1) {
       // pick i-1 is a chosen one (i-1 <= k-1): its neighbours are picks i-2 and i
       const float gap = prev - v;
-      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+      const float tol = RT_TOL * bnd + 9.5367431640625e-07f * fabsf(prev);
       amb = amb || !(fminf(gap_prev, gap) > tol);
       gap_prev = gap;
     }
     prev = v;
   }
   if (picks == k) {                            // E == k: the last chosen score has no lower neighbour
-    const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+    const float tol = RT_TOL * bnd + 9.5367431640625e-07f * fabsf(prev);
     amb = amb || !(gap_prev > tol);
   }
 #pragma unroll
@@ -137,7 +159,7 @@ __device__ int route_token(const float (&s)[QE], float lmax, bool check, int E, 
     // candidates: every expert whose score is not clearly below the neighbourhood of the last pick
     // (the best unchosen score, or the k-th chosen one if every expert is chosen)
     const float thr = prev;
-    const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(thr));
+    const float margin = 2.0f * (RT_TOL * bnd + 9.5367431640625e-07f * fabsf(thr));
     int n = 0;
 #pragma unroll
     for (int q = 0; q < QE; ++q) {
@@ -299,32 +321,42 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
 }
 
 // Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][max(E,RT_CMAX)] |
-//              int cand[RT_TM][RT_CMAX] | int flag[RT_TM]
+//              int cand[RT_TM][RT_CMAX] | int flag[RT_TM] | float xn[RT_NW][RT_TM] |
+//              float wn[RT_NW][<= 16 NT]   (per-wave parts of |x_t|^2 and |w_e|^2)
 // RPW = tile rows routed per wave: 2 (a full 16-token tile; compile-time so that the two tokens'
 // dependency chains interleave) or 1 (tpb <= 8 tokens per block).
 // PRE: the fast scores (bias included) were already written to scores_in[T][E] by
-// gate_tile_kernel; this kernel only selects and runs the exact pass.  scores_in may be the same
-// buffer as scores_out: a token's scores are read before they are written.
+// gate_tile_kernel, and |x_t|^2, |w_e|^2 to norms[T + E]; this kernel only selects and runs the
+// exact pass.  scores_in may be the same buffer as scores_out: a token's scores are read before
+// they are written.
 template <bool BF16, int NT, int RPW, bool PRE>
 __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
-    int d, int E, int k, int renorm, int tpb, const float* scores_in, int32_t* __restrict__ topk_idx,
-    float* __restrict__ topk_w, float* scores_out) {
+    int d, int E, int k, int renorm, int tpb, const float* scores_in, const float* __restrict__ norms,
+    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* scores_out) {
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
+  // w w^T tiles: one per 16 experts, or, from 128 experts on, one per 64 (the four tiles added up:
+  // a diagonal entry is then the sum of four experts' |w_e|^2, still an upper bound of each, and
+  // the accumulators fit the register file beside the score tiles)
+  constexpr int WG = NT >= 8 ? 4 : 1;
+  constexpr int NWT = NT / WG;
+  constexpr int EP = NWT * 16;
   extern __shared__ __align__(16) unsigned char smem[];
   float* part = reinterpret_cast<float*>(smem);
   const int dn = E > RT_CMAX ? E : RT_CMAX;
   double* dpart = reinterpret_cast<double*>(smem + static_cast<size_t>(RT_NW) * RT_TM * E * 4);
   int* cand_all = reinterpret_cast<int*>(dpart + RT_NW * dn);
   int* flag = cand_all + RT_TM * RT_CMAX;
+  float* xn = reinterpret_cast<float*>(flag + RT_TM);
+  float* wn = xn + RT_NW * RT_TM;
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
   const int t0 = blockIdx.x * tpb;     // this block's tokens are tile rows [0, tpb)
   const int row16 = BF16 ? d / 8 : d / 4;
+  float w2max = 0.f;                   // max_e |w_e|^2 (bf16 layers; set before the routing loop)
   // fp32 scores of tile row `row` from the eight partial tiles (fixed order) plus the bias;
-  // returns the row's largest |logit| (before the bias)
+  // returns |x_t| * max_e |w_e| of the row's token
   auto fast_scores = [&](int row, float (&s)[QE]) -> float {
-    float la = 0.f;
 #pragma unroll
     for (int q = 0; q < QE; ++q) {
       const int e = lane + MOE_WAVE * q;
@@ -332,17 +364,22 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       if (e < E) {
         if constexpr (PRE) {
           v = scores_in[static_cast<int64_t>(t0 + row) * E + e];
-          la = fmaxf(la, fabsf(bias ? v - bias[e] : v));
         } else {
 #pragma unroll
           for (int w = 0; w < RT_NW; ++w) v += part[(w * RT_TM + row) * E + e];
-          la = fmaxf(la, fabsf(v));
           if (bias) v += bias[e];
         }
       }
       s[q] = v;
     }
-    return wave_max(la);
+    float x2 = 0.f;
+    if constexpr (PRE) {
+      x2 = norms[min(t0 + row, T - 1)];
+    } else {
+#pragma unroll
+      for (int w = 0; w < RT_NW; ++w) x2 += xn[w * RT_TM + row];
+    }
+    return sqrtf(x2 * w2max);
   };
 
   if (BF16) {
@@ -356,26 +393,31 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
       wrow[nt] = wg + static_cast<int64_t>(min(nt * 16 + r, E - 1)) * row16;
-    f32x4_t acc[NT];
+    f32x4_t acc[NT], accw[NWT];        // score tiles; w w^T tiles (their diagonals are |w_e|^2)
+    f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};   // x x^T tile
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NWT; ++i) accw[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
     const int c0 = wave * cw;
     const int c1 = min(row16, c0 + cw);
     // x comes from HBM and is read exactly once: a batch of RT_BATCH MFMA steps has all of its
     // x fragments requested before the first one is used, so each wave keeps 16 KiB in flight.
     // w_gate fragments come from L2 and are fetched per step.
-    for (int cb = c0; cb < c1; cb += 4 * RT_BATCH) {
-      uint4 a[RT_BATCH];
+    // (128 and more experts: shorter batches, the score and norm tiles take the registers)
+    constexpr int XB = NT >= 16 ? RT_BATCH / 4 : (NT >= 8 ? RT_BATCH / 2 : RT_BATCH);
+    for (int cb = c0; cb < c1; cb += 4 * XB) {
+      uint4 a[XB];
 #pragma unroll
-      for (int u = 0; u < RT_BATCH; ++u) {
+      for (int u = 0; u < XB; ++u) {
         const int cc = cb + 4 * u + kq;
         a[u] = xrow[min(cc, row16 - 1)];
       }
       // w_gate fragments: BSTEPS steps' worth (16 loads) are requested together
       constexpr int BSTEPS = NT >= 16 ? 1 : (NT <= 2 ? 8 : 16 / NT);
 #pragma unroll
-      for (int u0 = 0; u0 < RT_BATCH; u0 += BSTEPS) {
+      for (int u0 = 0; u0 < XB; u0 += BSTEPS) {
         uint4 b[BSTEPS][NT];
 #pragma unroll
         for (int u = 0; u < BSTEPS; ++u) {
@@ -388,11 +430,14 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
           if (cb + 4 * (u0 + u) < c1) {                // wave-uniform
             uint4 av = a[u0 + u];
             if (cb + 4 * (u0 + u) + kq >= row16) av = make_uint4(0, 0, 0, 0);
+            accx = rt_mfma(av, av, accx);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                                __builtin_bit_cast(bf16x8_t, b[u][nt]),
-                                                                acc[nt], 0, 0, 0);
+            for (int nt = 0; nt < NT; ++nt) {
+              acc[nt] = rt_mfma(av, b[u][nt], acc[nt]);
+              // (a chunk past the end of the row repeats the last one: |w_e|^2 comes out a little
+              // too large, which an upper bound may)
+              accw[nt / WG] = rt_mfma(b[u][nt], b[u][nt], accw[nt / WG]);
+            }
           }
         }
       }
@@ -406,8 +451,34 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
         for (int v = 0; v < 4; ++v) part[(wave * RT_TM + 4 * kq + v) * E + e] = acc[nt][v];
       }
     }
+    if (rt_diag_lane(lane)) {
+      xn[wave * RT_TM + r] = rt_diag(accx, lane);
+#pragma unroll
+      for (int i = 0; i < NWT; ++i) wn[wave * EP + i * 16 + r] = rt_diag(accw[i], lane);
+    }
     __syncthreads();
    }
+    // max_e |w_e|^2 (tile rows past E repeat expert E - 1)
+    {
+      float m = 0.f;
+      if constexpr (PRE) {
+        // the same grouping as the fast pass of this kernel would use (WG experts, 16 apart, added up)
+        for (int e = lane; e < EP; e += MOE_WAVE) {
+          float v = 0.f;
+#pragma unroll
+          for (int j = 0; j < WG; ++j) v += norms[T + min(((e >> 4) * WG + j) * 16 + (e & 15), E - 1)];
+          m = fmaxf(m, v);
+        }
+      } else {
+        for (int e = lane; e < EP; e += MOE_WAVE) {
+          float v = 0.f;
+#pragma unroll
+          for (int w = 0; w < RT_NW; ++w) v += wn[w * EP + e];
+          m = fmaxf(m, v);
+        }
+      }
+      w2max = wave_max(m);
+    }
     // ---- routing: tile rows are dealt to the waves ----------------------------------------------
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
@@ -417,8 +488,8 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       int amb = 0;
       if (t < T) {
         float s[QE];
-        const float lmax = fast_scores(row, s);
-        amb = route_token<QE>(s, lmax, true, E, k, renorm, t, cand_all + row * RT_CMAX, topk_idx,
+        const float bnd = fast_scores(row, s);
+        amb = route_token<QE>(s, bnd, true, E, k, renorm, t, cand_all + row * RT_CMAX, topk_idx,
                               topk_w, scores_out);
       }
       if (lane == 0) flag[row] = amb;
@@ -555,7 +626,7 @@ template <int LPT> __device__ __forceinline__ float group_max(float x) {
 // `commit`: this lane's token exists and writes its outputs (if it is not flagged).
 // Every lane of the wave must call this (it exchanges data between lanes).
 template <int S, int LPT>
-__device__ void select_tile(const float (&s)[S], float lmax, bool check, bool commit, int E, int k,
+__device__ void select_tile(const float (&s)[S], float bnd, bool check, bool commit, int E, int k,
                             int renorm, int64_t t, int row, float* __restrict__ picks,
                             int* __restrict__ cand_row, int* __restrict__ ccount_row,
                             int* __restrict__ plist, int* __restrict__ pcount,
@@ -644,19 +715,19 @@ __device__ void select_tile(const float (&s)[S], float lmax, bool check, bool co
     if (i >= 1) {
       // pick i-1 is a chosen one: its neighbours are picks i-2 and i
       const float gap = prev - bv;
-      const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+      const float tol = RT_TOL * bnd + 9.5367431640625e-07f * fabsf(prev);
       amb = amb || !(fminf(gap_prev, gap) > tol);
       gap_prev = gap;
     }
     prev = bv;
   }
   if (npick == k) {                            // E == k: the last chosen score has no lower neighbour
-    const float tol = 6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev);
+    const float tol = RT_TOL * bnd + 9.5367431640625e-07f * fabsf(prev);
     amb = amb || !(gap_prev > tol);
   }
   amb = amb && check;
   // candidates of a flagged token: every expert not clearly below the last pick
-  const float margin = 2.0f * (6.103515625e-05f * lmax + 9.5367431640625e-07f * fabsf(prev));
+  const float margin = 2.0f * (RT_TOL * bnd + 9.5367431640625e-07f * fabsf(prev));
   int n_local = 0;
   if (amb) {
 #pragma unroll
@@ -723,7 +794,9 @@ struct RouteTileLds {
   static constexpr int FLIST = PLIST + TILES * 16 * RT_CMAX * 4;            // int [16 TILES] + two counts
   static constexpr int DPART = 0;   // double [RT_NW][max(E, RT_CMAX)]: the exact pass's partial sums also
                                     // alias the stages (nothing there is live once the scores are read back)
-  static constexpr int TOTAL = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;
+  static constexpr int XN = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;   // float [RT_NW][16]: parts of |x_t|^2
+  static constexpr int WN = XN + RT_NW * 16 * 4;                            // float [KS][16 NT]: parts of |w_e|^2
+  static constexpr int TOTAL = WN + KS * NT * 16 * 4;
   static_assert(RT_NW * (NT * 16 > RT_CMAX ? NT * 16 : RT_CMAX) * 8 <= RING, "exact-pass sums fit the ring");
   static_assert(TOTAL <= 160 * 1024, "LDS of the large-batch routing kernel");
 };
@@ -798,9 +871,15 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 #pragma unroll
   for (int j = 0; j < 2; ++j) koff[j] = ((j * 4 + kgrp) ^ f) << 4;
 
-  f32x4_t acc[NT];
+  // score tiles; the x x^T tile; w w^T tiles (their diagonals are |w_e|^2): the TILES waves of a
+  // slice see the same w_gate rows, so wave `tile` takes the expert tiles nt = tile, tile + TILES, ...
+  constexpr int NWT = (NT + TILES - 1) / TILES;
+  f32x4_t acc[NT], accw[NWT];
+  f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < NWT; ++i) accw[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   using std::integral_constant;
   // prologue: the first DIST stages; then stage kt waits for its own loads (up to DIST - 1 later
@@ -822,10 +901,13 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const bf16x8_t xf = __builtin_bit_cast(bf16x8_t, a[SLOT][j]);
+      accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, xf, accx, 0, 0, 0);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const bf16x8_t wf = *reinterpret_cast<const bf16x8_t*>(sb + nt * 16 * 128 + koff[j]);
         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nt], 0, 0, 0);
+        if (nt % TILES == tile)          // wave-uniform
+          accw[nt / TILES] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, wf, accw[nt / TILES], 0, 0, 0);
       }
     }
   };
@@ -845,6 +927,16 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) part[((wave * NT + nt) * 4 + v) * MOE_WAVE + lane] = acc[nt][v];
+  float* xn = reinterpret_cast<float*>(smem + L::XN);
+  float* wn = reinterpret_cast<float*>(smem + L::WN);
+  if (rt_diag_lane(lane)) {
+    xn[wave * 16 + tok] = rt_diag(accx, lane);
+#pragma unroll
+    for (int i = 0; i < NWT; ++i) {
+      const int nt = i * TILES + tile;
+      if (nt < NT) wn[(ks * NT + nt) * 16 + tok] = rt_diag(accw[i], lane);
+    }
+  }
   for (int i = threadIdx.x; i < TILES * 16; i += RT_THREADS) ccount[i] = 0;
   __syncthreads();
   const int tl = lane / LPT, j = lane % LPT;
@@ -853,7 +945,6 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   const int64_t t = t0 + row;
   const bool t_ok = t < T;
   float s[S];
-  float la = 0.f;
 #pragma unroll
   for (int q = 0; q < S; ++q) {
     const int e = j * S + q;
@@ -861,15 +952,23 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
     float sum = 0.f;
 #pragma unroll
     for (int sl = 0; sl < KS; ++sl) sum += part[(sl * TILES + tile) * NT * 4 * MOE_WAVE + at];
-    if (e < E) {
-      la = fmaxf(la, fabsf(sum));
-      if (bias) sum += bias[e];
-    }
+    if (e < E && bias) sum += bias[e];
     s[q] = sum;
   }
-  la = group_max<LPT>(la);
+  // |x_t| * max_e |w_e| (stage rows past E repeat expert E - 1)
+  float w2 = 0.f, x2 = 0.f;
+  for (int e = lane; e < NT * 16; e += MOE_WAVE) {
+    float v = 0.f;
+#pragma unroll
+    for (int sl = 0; sl < KS; ++sl) v += wn[sl * NT * 16 + e];
+    w2 = fmaxf(w2, v);
+  }
+  w2 = wave_max(w2);
+#pragma unroll
+  for (int sl = 0; sl < KS; ++sl) x2 += xn[(sl * TILES + tile) * 16 + trow];
+  const float bnd = sqrtf(x2 * w2);
   float* picks = reinterpret_cast<float*>(smem + L::PICKS) + wave * 2 * (RT_KSEL + 1) * 16;
-  select_tile<S, LPT>(s, la, true, t_ok, E, k, renorm, t, row, picks, cand_all + row * RT_CMAX,
+  select_tile<S, LPT>(s, bnd, true, t_ok, E, k, renorm, t, row, picks, cand_all + row * RT_CMAX,
                       ccount + row, plist, pcount, flist, fcount, topk_idx, topk_w, scores_out);
   __syncthreads();
   // ---- exact pass for the flagged tokens (block-uniform control flow) ----------------------------
@@ -941,8 +1040,9 @@ constexpr int GT_BATCH = 8;   // MFMA steps whose fragments (x and up to four w_
 template <int GNT>
 __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
-    int d, int E, float* __restrict__ scores) {
+    int d, int E, float* __restrict__ scores, float* __restrict__ norms) {
   __shared__ float part[RT_NW][RT_TM][16 * GNT];
+  __shared__ float xn[RT_NW][RT_TM], wn[RT_NW][16 * GNT];
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
   const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * (16 * GNT);
@@ -951,11 +1051,12 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
   const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
   const uint4* xrow = x + static_cast<int64_t>(min(t0 + r, T - 1)) * row16;
   const uint4* wrow[GNT];
-  f32x4_t acc[GNT];
+  f32x4_t acc[GNT], accw[GNT];
+  f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int nt = 0; nt < GNT; ++nt) {
     wrow[nt] = wg + static_cast<int64_t>(min(e0 + nt * 16 + r, E - 1)) * row16;
-    acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    acc[nt] = accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
   const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
   const int c0 = wave * cw;
@@ -974,11 +1075,12 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
       if (cb + 4 * u < c1) {                         // wave-uniform
         uint4 av = a[u];
         if (cb + 4 * u + kq >= row16) av = make_uint4(0, 0, 0, 0);
+        accx = rt_mfma(av, av, accx);
 #pragma unroll
-        for (int nt = 0; nt < GNT; ++nt)
-          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, av),
-                                                            __builtin_bit_cast(bf16x8_t, b[u][nt]),
-                                                            acc[nt], 0, 0, 0);
+        for (int nt = 0; nt < GNT; ++nt) {
+          acc[nt] = rt_mfma(av, b[u][nt], acc[nt]);
+          accw[nt] = rt_mfma(b[u][nt], b[u][nt], accw[nt]);   // (past the end: see route_kernel)
+        }
       }
     }
   }
@@ -987,7 +1089,29 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
   for (int nt = 0; nt < GNT; ++nt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][nt * 16 + r] = acc[nt][v];
+  if (rt_diag_lane(lane)) {
+    xn[wave][r] = rt_diag(accx, lane);
+#pragma unroll
+    for (int nt = 0; nt < GNT; ++nt) wn[wave][nt * 16 + r] = rt_diag(accw[nt], lane);
+  }
   __syncthreads();
+  // |x_t|^2 from the blocks of the first expert tile, |w_e|^2 from those of the first token tile
+  {
+    const int i = static_cast<int>(threadIdx.x);
+    if (blockIdx.y == 0 && i < RT_TM && t0 + i < T) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < RT_NW; ++w) v += xn[w][i];
+      norms[t0 + i] = v;
+    }
+    const int ee = i - MOE_WAVE;
+    if (blockIdx.x == 0 && ee >= 0 && ee < 16 * GNT && e0 + ee < E) {
+      float v = 0.f;
+#pragma unroll
+      for (int w = 0; w < RT_NW; ++w) v += wn[w][ee];
+      norms[T + e0 + ee] = v;
+    }
+  }
   for (int i = static_cast<int>(threadIdx.x); i < RT_TM * 16 * GNT; i += RT_THREADS) {
     const int row = i / (16 * GNT), ee = i % (16 * GNT);
     const int64_t t = t0 + row;
@@ -1004,14 +1128,16 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
 
 static size_t route_lds_bytes(int E) {
   const size_t dn = E > RT_CMAX ? E : RT_CMAX;
+  size_t ep = 16;                      // 16 NT of the kernel that serves E experts
+  while (ep < static_cast<size_t>(E)) ep <<= 1;
   return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 +
-         RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int);
+         RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int) + RT_NW * (RT_TM + ep) * sizeof(float);
 }
 
 template <bool BF16, int NT, int RPW, bool PRE>
 static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                            int32_t* idx, float* w, const float* scores_in, float* scores, int tpb,
-                            hipStream_t st) {
+                            int32_t* idx, float* w, const float* scores_in, const float* norms,
+                            float* scores, int tpb, hipStream_t st) {
   static LdsOnce once;
   if (ensure_dynamic_lds(once, reinterpret_cast<const void*>(route_kernel<BF16, NT, RPW, PRE>),
                          static_cast<int>(route_lds_bytes(MOE_MAX_E))) != MOE_OK)
@@ -1020,15 +1146,16 @@ static int launch_route_rpw(const moe_shape_t* s, const void* x, const void* wg,
   hipLaunchKernelGGL((route_kernel<BF16, NT, RPW, PRE>), dim3(grid), dim3(RT_THREADS),
                      route_lds_bytes(s->E), st, static_cast<const uint4*>(x),
                      static_cast<const uint4*>(wg), bias, s->T, s->d, s->E, s->k, s->renorm, tpb,
-                     scores_in, idx, w, scores);
+                     scores_in, norms, idx, w, scores);
   return launch_status();
 }
 
 // scratch: T x E floats the call may use between its kernels (the caller's score output or its
-// workspace), or null.
+// workspace), or null; norms: T + E floats of the workspace for |x_t|^2 and |w_e|^2, or null.
 template <bool BF16, int NT>
 static int launch_route(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                        int32_t* idx, float* w, float* scores, float* scratch, hipStream_t st) {
+                        int32_t* idx, float* w, float* scores, float* scratch, float* norms,
+                        hipStream_t st) {
   // Tokens per block: a full 16-row tile when that still gives every CU a block (every wave then
   // has its whole slice of the tile's rows, 16 KiB at d = 4096, requested at once); fewer (the other
   // tile rows idle) for smaller batches, where latency, not MFMA use, is what counts.
@@ -1038,25 +1165,25 @@ static int launch_route(const moe_shape_t* s, const void* x, const void* wg, con
   int tpb = RT_TM;
   while (tpb > 1 && (s->T + tpb - 1) / tpb < GRID_TARGET) tpb >>= 1;
   if (tpb == RT_TM)
-    return launch_route_rpw<BF16, NT, 2, false>(s, x, wg, bias, idx, w, nullptr, scores, tpb, st);
+    return launch_route_rpw<BF16, NT, 2, false>(s, x, wg, bias, idx, w, nullptr, nullptr, scores, tpb, st);
   if constexpr (BF16) {
     // gate product spread over the chip first, if there is somewhere to put the scores and the
     // gate matrix is large enough (256 KB: 8 us through one CU) to pay for the second launch
-    if (scratch && s->T <= RT_PRE_MAX_T && static_cast<int64_t>(s->E) * s->d * 2 >= 256 * 1024) {
+    if (scratch && norms && s->T <= RT_PRE_MAX_T && static_cast<int64_t>(s->E) * s->d * 2 >= 256 * 1024) {
       const int t_tiles = (s->T + RT_TM - 1) / RT_TM;
       if (static_cast<int64_t>(t_tiles) * ((s->E + 63) / 64) >= 256)
         hipLaunchKernelGGL(gate_tile_kernel<4>, dim3(t_tiles, (s->E + 63) / 64), dim3(RT_THREADS), 0, st,
                            static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T,
-                           s->d, s->E, scratch);
+                           s->d, s->E, scratch, norms);
       else
         hipLaunchKernelGGL(gate_tile_kernel<1>, dim3(t_tiles, (s->E + 15) / 16), dim3(RT_THREADS), 0, st,
                            static_cast<const uint4*>(x), static_cast<const uint4*>(wg), bias, s->T,
-                           s->d, s->E, scratch);
+                           s->d, s->E, scratch, norms);
       if (launch_status() != MOE_OK) return MOE_ERR_HIP;
-      return launch_route_rpw<BF16, NT, 1, true>(s, x, wg, bias, idx, w, scratch, scores, tpb, st);
+      return launch_route_rpw<BF16, NT, 1, true>(s, x, wg, bias, idx, w, scratch, norms, scores, tpb, st);
     }
   }
-  return launch_route_rpw<BF16, NT, 1, false>(s, x, wg, bias, idx, w, nullptr, scores, tpb, st);
+  return launch_route_rpw<BF16, NT, 1, false>(s, x, wg, bias, idx, w, nullptr, nullptr, scores, tpb, st);
 }
 
 template <int NT, int TILES>
@@ -1122,10 +1249,11 @@ static bool try_route_tile(const moe_shape_t* s, const void* x, const void* wg, 
 
 template <int NT>
 static int launch_route_bf16(const moe_shape_t* s, const void* x, const void* wg, const float* bias,
-                             int32_t* idx, float* w, float* scores, float* scratch, hipStream_t st) {
+                             int32_t* idx, float* w, float* scores, float* scratch, float* norms,
+                             hipStream_t st) {
   int rc = MOE_OK;
   if (try_route_tile<NT>(s, x, wg, bias, idx, w, scores, st, &rc)) return rc;
-  return launch_route<true, NT>(s, x, wg, bias, idx, w, scores, scratch, st);
+  return launch_route<true, NT>(s, x, wg, bias, idx, w, scores, scratch, norms, st);
 }
 
 }  // namespace moe
@@ -1141,21 +1269,29 @@ static int route_impl(const moe_shape_t* shape, const void* x, const void* w_gat
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const int E = shape->E;
   // somewhere to keep T x E fast scores between two kernels: the caller's score output, else its
-  // workspace if that is large enough
+  // workspace if that is large enough; and T + E floats of the workspace for the norms
   float* scratch = scores_out;
-  if (!scratch && workspace && moe::aligned16(workspace) &&
-      workspace_bytes >= static_cast<size_t>(shape->T) * E * sizeof(float))
-    scratch = static_cast<float*>(workspace);
-  if (shape->dtype == MOE_BF16) {
-    if (E <= 16) return moe::launch_route_bf16<1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
-    if (E <= 32) return moe::launch_route_bf16<2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
-    if (E <= 64) return moe::launch_route_bf16<4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
-    if (E <= 128) return moe::launch_route_bf16<8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
-    return moe::launch_route_bf16<16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, st);
+  float* norms = nullptr;
+  const size_t score_bytes = static_cast<size_t>(shape->T) * E * sizeof(float);
+  const size_t norm_bytes = (static_cast<size_t>(shape->T) + E) * sizeof(float);
+  if (workspace && moe::aligned16(workspace)) {
+    if (scratch) {
+      if (workspace_bytes >= norm_bytes) norms = static_cast<float*>(workspace);
+    } else if (workspace_bytes >= score_bytes + norm_bytes) {
+      scratch = static_cast<float*>(workspace);
+      norms = scratch + static_cast<size_t>(shape->T) * E;
+    }
   }
-  if (E <= 64) return moe::launch_route<false, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
-  if (E <= 128) return moe::launch_route<false, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
-  return moe::launch_route<false, 16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, st);
+  if (shape->dtype == MOE_BF16) {
+    if (E <= 16) return moe::launch_route_bf16<1>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, norms, st);
+    if (E <= 32) return moe::launch_route_bf16<2>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, norms, st);
+    if (E <= 64) return moe::launch_route_bf16<4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, norms, st);
+    if (E <= 128) return moe::launch_route_bf16<8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, norms, st);
+    return moe::launch_route_bf16<16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, scratch, norms, st);
+  }
+  if (E <= 64) return moe::launch_route<false, 4>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, nullptr, st);
+  if (E <= 128) return moe::launch_route<false, 8>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, nullptr, st);
+  return moe::launch_route<false, 16>(shape, x, w_gate, gate_bias, topk_idx, topk_w, scores_out, nullptr, nullptr, st);
 }
 
 extern "C" int moe_route(const moe_shape_t* shape, const void* x, const void* w_gate,

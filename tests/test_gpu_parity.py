@@ -133,10 +133,61 @@ def test_route_near_ties_are_decided_like_the_oracle():
     check_route(cfg, L["x"], wg, bias)
 
 
-# Batches large enough for the large-batch routing kernel (at least 256 blocks of 2, 4 or 8 token
-# tiles, at least 96 if the gate matrix has 128 KB or more; 4 or 8 tiles for 65 to 128 experts, 4 for more;
-# k <= 16, whole 64-element stages per slice of the hidden dimension).
-# The hidden size is small so that the oracle stays fast.  T is never a multiple of the block.
+def cancelling_tokens(T, d, E, seed):
+    """bf16 inputs whose large terms cancel: the first 3/8 of a token are A*u, the next 3/8 are
+    -A*u, against gate rows that repeat the same positive vector on both parts, so those products
+    add up to exactly zero; the logit is what the last quarter contributes, thousands of times
+    smaller than the partial sums on the way.  Experts 2i and 2i+1 differ in one element of the last
+    quarter by one bf16 step: their logits are a hair apart, which is larger depends on the token,
+    and every token's leading experts are such a pair."""
+    rng = np.random.default_rng(seed)
+    m = 3 * d // 8
+    u = np.abs(rng.standard_normal((T, m), dtype=np.float32)) * 16.0
+    sig = rng.standard_normal((T, d - 2 * m), dtype=np.float32) * 0.02
+    x = si.f32_to_bf16_bits(np.concatenate([u, -u, sig], axis=1))
+    x[:, m:2 * m] = x[:, :m] ^ np.uint16(0x8000)              # exactly the negated bf16 values
+    c = np.abs(rng.standard_normal(m, dtype=np.float32)) / 16.0
+    g = rng.standard_normal((E, d - 2 * m), dtype=np.float32) / 32.0
+    g[1::2] = g[0::2]
+    wg = si.f32_to_bf16_bits(np.concatenate([np.tile(c, (E, 1)), np.tile(c, (E, 1)), g], axis=1))
+    wg[1::2, 2 * m + 5] += 1                                 # one bf16 step in one element
+    return x, wg
+
+
+@pytest.mark.parametrize("T,d,E,k,ws", [
+    (200, 1024, 8, 2, False),      # per-tile kernel
+    (2000, 1024, 8, 2, False),     # large-batch kernel, 2 tiles per block
+    (3000, 1024, 64, 6, False),    # ... 64 experts
+    (100, 1024, 128, 8, True),     # gate product as a kernel of its own, norms through the workspace
+    (40, 2048, 256, 8, False),     # per-tile kernel, 256 experts (grouped norm tiles)
+])
+def test_route_when_large_terms_cancel(T, d, E, k, ws):
+    """The fast pass's rounding errors follow the size of the terms it adds, not of their sum: a
+    margin taken from the logits would let these tokens through with the wrong order."""
+    cfg = si.small_config(T=T, d=d, E=E, k=k, F=64, renorm=1)
+    x, wg = cancelling_tokens(T, d, E, seed=77)
+    ridx, rw, rsc = orc.route(x, wg, k, 1, None)
+    # not vacuous: the gap between experts 0 and 1 is far below what an fp32 sum of these terms
+    # can resolve, and both orders occur
+    gap = np.abs(rsc[:, 0] - rsc[:, 1])
+    xf, wf = si.bf16_bits_to_f32(x), si.bf16_bits_to_f32(wg)
+    part = np.abs(np.cumsum(xf[:8].astype(np.float64) * wf[0].astype(np.float64), axis=1)).max(axis=1)
+    assert np.all(gap[:8] > 0) and np.all(gap[:8] < part * 2.0 ** -24)
+    assert 0.2 < (rsc[:, 0] > rsc[:, 1]).mean() < 0.8
+    if ws:
+        idx, w, sc = gpu_route_ws(cfg, x, wg, None, True, True)
+    else:
+        idx, w, sc = gpu_route(cfg, x, wg, None)
+    bad = np.nonzero((idx != ridx).any(axis=1))[0]
+    assert bad.size == 0, f"top-k differs on rows {bad[:8]} gpu {idx[bad[:3]]} ref {ridx[bad[:3]]}"
+    assert np.all(np.abs(w - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+
+
+# Batches large enough for the large-batch routing kernel (from 96 blocks of 2, 4 or 8 token tiles on;
+# gate matrices of at most 128 KB take the fewest tiles per block, larger ones the most that still
+# give 256 blocks; 4 or 8 tiles for 65 to 128 experts, 4 for more; k <= 16, whole 64-element stages
+# per slice of the hidden dimension).  The hidden size is small so that the oracle stays fast,
+# except where only a large gate matrix reaches a form.  T is never a multiple of the block.
 BIG_ROUTE_CASES = [
     dict(T=8195, d=256, E=64, k=6, renorm=1),      # 2 tiles per block, 4 slices
     dict(T=8200, d=512, E=40, k=8, renorm=0),      # experts not a multiple of 16
@@ -144,8 +195,12 @@ BIG_ROUTE_CASES = [
     dict(T=9000, d=768, E=16, k=16, renorm=0),     # the largest k this path takes, k = E
     dict(T=16400, d=256, E=16, k=1, renorm=1),     # 4 tiles per block, 2 slices
     dict(T=16390, d=384, E=33, k=3, renorm=1),
-    dict(T=32800, d=128, E=8, k=2, renorm=1),      # 8 tiles per block
+    dict(T=32800, d=128, E=8, k=2, renorm=1),
     dict(T=33000, d=64, E=64, k=15, renorm=0),     # one stage
+    dict(T=32800, d=5120, E=16, k=1, renorm=0),    # 160 KB gate matrix: 8 tiles per block, up to 16 experts
+    dict(T=16400, d=5120, E=16, k=2, renorm=1),    # ... 4 tiles per block
+    dict(T=32800, d=2304, E=32, k=4, renorm=1),    # 8 tiles per block, up to 32 experts
+    dict(T=32800, d=1088, E=64, k=6, renorm=0),    # 8 tiles per block, up to 64 experts
     dict(T=16400, d=256, E=128, k=8, renorm=1),    # more than 64 experts: 4 tiles per block only
     dict(T=16390, d=128, E=100, k=6, renorm=0),
     dict(T=16400, d=256, E=65, k=16, renorm=1),
@@ -251,9 +306,12 @@ def test_route_with_workspace_matches_oracle_and_plain_route(case):
             idx, w, sc = gpu_route_ws(cfg, x, wg, b, with_ws, with_scores)
             assert np.array_equal(idx, ridx), (with_ws, with_scores)
             assert np.all(np.abs(w - rw) <= 1e-5 * np.abs(rw) + 1e-9)
-            assert np.array_equal(w, pw)            # same scores, same arithmetic: same bits
+            # the two forms take the choice on the same fast scores and re-score near-ties exactly;
+            # which tokens count as near-ties may differ in the last bits of the margin, so weights
+            # and scores agree to the oracle's tolerance rather than bit for bit
+            assert np.all(np.abs(w - pw) <= 1e-5 * np.abs(pw) + 1e-9)
             if with_scores:
-                assert np.array_equal(sc, psc)
+                assert np.all(np.abs(sc - psc) <= 1e-5 * np.abs(psc).max(axis=1, keepdims=True))
 
 
 def test_route_ws_without_usable_workspace_is_plain_route():
