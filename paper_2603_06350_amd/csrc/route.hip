@@ -24,7 +24,7 @@
 // rounding errors of the fast pass scale with the magnitude of the products and partial sums,
 // which the product of the norms bounds, not with the magnitude of the result: a token whose
 // large terms cancel has tiny logits and large errors.  Both norms come out of the same pass
-// (the diagonals of x x^T and w w^T tiles on the matrix cores).  For inputs without cancellation
+// (sums of squares of the fragments it multiplies).  For inputs without cancellation
 // the margin is about 2^-14 of the largest logit, some 60 times the fast pass's typical error.
 // For ambiguous tokens (about
 // 1% for 64 experts, ~0.03% for 8) the whole block re-scores the experts that could
@@ -63,13 +63,25 @@ constexpr int RT_CMAX = 16;   // candidate experts re-scored exactly for an ambi
 // Two fast scores closer than RT_TOL * |x_t| * max_e |w_e| are re-scored exactly.
 constexpr float RT_TOL = 1.9073486328125e-06f;   // 2^-19
 
-// Element (i, i) of a 16 x 16 MFMA result tile (a lane holds column lane & 15, rows
-// 4 (lane >> 4) + v): held by the lanes with (lane & 15) >> 2 == lane >> 4, in component lane & 3.
-__device__ __forceinline__ bool rt_diag_lane(int lane) { return ((lane & 15) >> 2) == (lane >> 4); }
-__device__ __forceinline__ float rt_diag(const f32x4_t& a, int lane) {
-  const int v = lane & 3;
-  return v == 0 ? a[0] : (v == 1 ? a[1] : (v == 2 ? a[2] : a[3]));
+// acc + the sum of the squares of the eight bf16 values of a fragment (v_dot2c_f32_bf16: vector ALU
+// work that issues in the shadow of the MFMAs; as separate x x^T and w w^T MFMA tiles the norms
+// cost the large-batch kernel 4 % at 8 experts).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+// Four running sums, one per dword of the fragment, so that consecutive fragments do not form one
+// long chain of dependent instructions; rt_sumsq_total adds them up.
+struct RtSumSq {
+  float a = 0.f, b = 0.f, c = 0.f, d = 0.f;
+};
+__device__ __forceinline__ void rt_sumsq(uint4 v, RtSumSq& s) {
+  s.a = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v.x), __builtin_bit_cast(bf16x2_t, v.x), s.a, false);
+  s.b = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v.y), __builtin_bit_cast(bf16x2_t, v.y), s.b, false);
+  s.c = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v.z), __builtin_bit_cast(bf16x2_t, v.z), s.c, false);
+  s.d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, v.w), __builtin_bit_cast(bf16x2_t, v.w), s.d, false);
 }
+__device__ __forceinline__ float rt_sumsq_total(const RtSumSq& s) { return (s.a + s.b) + (s.c + s.d); }
+// (The four lanes l, l + 16, l + 32, l + 48 hold the four 16-byte chunks of a row's k-step, so a
+// row's sum of squares is spread over them: each writes its part to LDS and the reader adds the
+// four up; exchanging them between lanes first cost a microsecond of latency per block.)
 __device__ __forceinline__ f32x4_t rt_mfma(uint4 a, uint4 b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                  __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
@@ -321,8 +333,8 @@ __device__ void exact_partial(const uint4* __restrict__ xrow, const uint4* __res
 }
 
 // Dynamic LDS: float part[RT_NW][RT_TM][E] | double dpart[RT_NW][max(E,RT_CMAX)] |
-//              int cand[RT_TM][RT_CMAX] | int flag[RT_TM] | float xn[RT_NW][RT_TM] |
-//              float wn[RT_NW][<= 16 NT]   (per-wave parts of |x_t|^2 and |w_e|^2)
+//              int cand[RT_TM][RT_CMAX] | int flag[RT_TM] | float xn[RT_NW * 4][RT_TM] |
+//              float wn[RT_NW * 4][<= 16 NT]   (per wave and lane group: parts of |x_t|^2 and |w_e|^2)
 // RPW = tile rows routed per wave: 2 (a full 16-token tile; compile-time so that the two tokens'
 // dependency chains interleave) or 1 (tpb <= 8 tokens per block).
 // PRE: the fast scores (bias included) were already written to scores_in[T][E] by
@@ -335,9 +347,8 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
     int d, int E, int k, int renorm, int tpb, const float* scores_in, const float* __restrict__ norms,
     int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, float* scores_out) {
   constexpr int QE = NT >= 4 ? NT / 4 : 1;
-  // w w^T tiles: one per 16 experts, or, from 128 experts on, one per 64 (the four tiles added up:
-  // a diagonal entry is then the sum of four experts' |w_e|^2, still an upper bound of each, and
-  // the accumulators fit the register file beside the score tiles)
+  // |w_e|^2 sums: one per 16 experts, or, from 128 experts on, one per 64 (four experts, 16 apart,
+  // added up: still an upper bound of each)
   constexpr int WG = NT >= 8 ? 4 : 1;
   constexpr int NWT = NT / WG;
   constexpr int EP = NWT * 16;
@@ -348,7 +359,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
   int* cand_all = reinterpret_cast<int*>(dpart + RT_NW * dn);
   int* flag = cand_all + RT_TM * RT_CMAX;
   float* xn = reinterpret_cast<float*>(flag + RT_TM);
-  float* wn = xn + RT_NW * RT_TM;
+  float* wn = xn + RT_NW * 4 * RT_TM;
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
   const int t0 = blockIdx.x * tpb;     // this block's tokens are tile rows [0, tpb)
@@ -377,7 +388,7 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
       x2 = norms[min(t0 + row, T - 1)];
     } else {
 #pragma unroll
-      for (int w = 0; w < RT_NW; ++w) x2 += xn[w * RT_TM + row];
+      for (int w = 0; w < RT_NW * 4; ++w) x2 += xn[w * RT_TM + row];
     }
     return sqrtf(x2 * w2max);
   };
@@ -393,12 +404,10 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
       wrow[nt] = wg + static_cast<int64_t>(min(nt * 16 + r, E - 1)) * row16;
-    f32x4_t acc[NT], accw[NWT];        // score tiles; w w^T tiles (their diagonals are |w_e|^2)
-    f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};   // x x^T tile
+    f32x4_t acc[NT];                   // score tiles
+    RtSumSq x2, w2[NWT];               // this lane's part of |x_t|^2 (token r) and |w_e|^2 (experts 16 i + r)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < NWT; ++i) accw[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
     const int c0 = wave * cw;
     const int c1 = min(row16, c0 + cw);
@@ -430,13 +439,13 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
           if (cb + 4 * (u0 + u) < c1) {                // wave-uniform
             uint4 av = a[u0 + u];
             if (cb + 4 * (u0 + u) + kq >= row16) av = make_uint4(0, 0, 0, 0);
-            accx = rt_mfma(av, av, accx);
+            rt_sumsq(av, x2);
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
               acc[nt] = rt_mfma(av, b[u][nt], acc[nt]);
               // (a chunk past the end of the row repeats the last one: |w_e|^2 comes out a little
               // too large, which an upper bound may)
-              accw[nt / WG] = rt_mfma(b[u][nt], b[u][nt], accw[nt / WG]);
+              rt_sumsq(b[u][nt], w2[nt / WG]);
             }
           }
         }
@@ -451,11 +460,9 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
         for (int v = 0; v < 4; ++v) part[(wave * RT_TM + 4 * kq + v) * E + e] = acc[nt][v];
       }
     }
-    if (rt_diag_lane(lane)) {
-      xn[wave * RT_TM + r] = rt_diag(accx, lane);
+    xn[(wave * 4 + kq) * RT_TM + r] = rt_sumsq_total(x2);
 #pragma unroll
-      for (int i = 0; i < NWT; ++i) wn[wave * EP + i * 16 + r] = rt_diag(accw[i], lane);
-    }
+    for (int i = 0; i < NWT; ++i) wn[(wave * 4 + kq) * EP + i * 16 + r] = rt_sumsq_total(w2[i]);
     __syncthreads();
    }
     // max_e |w_e|^2 (tile rows past E repeat expert E - 1)
@@ -473,11 +480,11 @@ __global__ __launch_bounds__(RT_THREADS) void route_kernel(
         for (int e = lane; e < EP; e += MOE_WAVE) {
           float v = 0.f;
 #pragma unroll
-          for (int w = 0; w < RT_NW; ++w) v += wn[w * EP + e];
+          for (int w = 0; w < RT_NW * 4; ++w) v += wn[w * EP + e];
           m = fmaxf(m, v);
         }
       }
-      w2max = wave_max(m);
+      w2max = wave_max_dpp(m);
     }
     // ---- routing: tile rows are dealt to the waves ----------------------------------------------
 #pragma unroll
@@ -794,9 +801,10 @@ struct RouteTileLds {
   static constexpr int FLIST = PLIST + TILES * 16 * RT_CMAX * 4;            // int [16 TILES] + two counts
   static constexpr int DPART = 0;   // double [RT_NW][max(E, RT_CMAX)]: the exact pass's partial sums also
                                     // alias the stages (nothing there is live once the scores are read back)
-  static constexpr int XN = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;   // float [RT_NW][16]: parts of |x_t|^2
-  static constexpr int WN = XN + RT_NW * 16 * 4;                            // float [KS][16 NT]: parts of |w_e|^2
-  static constexpr int TOTAL = WN + KS * NT * 16 * 4;
+  static constexpr int XN = (FLIST + TILES * 16 * 4 + 16 + 15) / 16 * 16;   // float [RT_NW][4][16]: parts of |x_t|^2
+  static constexpr int WN = XN + RT_NW * 4 * 16 * 4;                        // float [KS][NT][WNG][16]: parts of |w_e|^2
+  static constexpr int WNG = NT >= 16 ? 1 : 4;    // lane groups kept apart (256 experts: no room, added up first)
+  static constexpr int TOTAL = WN + KS * NT * WNG * 16 * 4;
   static_assert(RT_NW * (NT * 16 > RT_CMAX ? NT * 16 : RT_CMAX) * 8 <= RING, "exact-pass sums fit the ring");
   static_assert(TOTAL <= 160 * 1024, "LDS of the large-batch routing kernel");
 };
@@ -871,15 +879,14 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 #pragma unroll
   for (int j = 0; j < 2; ++j) koff[j] = ((j * 4 + kgrp) ^ f) << 4;
 
-  // score tiles; the x x^T tile; w w^T tiles (their diagonals are |w_e|^2): the TILES waves of a
-  // slice see the same w_gate rows, so wave `tile` takes the expert tiles nt = tile, tile + TILES, ...
+  // score tiles; this lane's part of |x_t|^2 (token tok) and of |w_e|^2 (experts 16 nt + tok): the
+  // TILES waves of a slice see the same w_gate rows, so wave `tile` takes the expert tiles
+  // nt = tile, tile + TILES, ...
   constexpr int NWT = (NT + TILES - 1) / TILES;
-  f32x4_t acc[NT], accw[NWT];
-  f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  f32x4_t acc[NT];
+  RtSumSq x2p, w2p[NWT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int i = 0; i < NWT; ++i) accw[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   using std::integral_constant;
   // prologue: the first DIST stages; then stage kt waits for its own loads (up to DIST - 1 later
@@ -901,13 +908,13 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const bf16x8_t xf = __builtin_bit_cast(bf16x8_t, a[SLOT][j]);
-      accx = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf, xf, accx, 0, 0, 0);
+      rt_sumsq(a[SLOT][j], x2p);
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         const bf16x8_t wf = *reinterpret_cast<const bf16x8_t*>(sb + nt * 16 * 128 + koff[j]);
         acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nt], 0, 0, 0);
         if (nt % TILES == tile)          // wave-uniform
-          accw[nt / TILES] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, wf, accw[nt / TILES], 0, 0, 0);
+          rt_sumsq(__builtin_bit_cast(uint4, wf), w2p[nt / TILES]);
       }
     }
   };
@@ -929,12 +936,17 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
     for (int v = 0; v < 4; ++v) part[((wave * NT + nt) * 4 + v) * MOE_WAVE + lane] = acc[nt][v];
   float* xn = reinterpret_cast<float*>(smem + L::XN);
   float* wn = reinterpret_cast<float*>(smem + L::WN);
-  if (rt_diag_lane(lane)) {
-    xn[wave * 16 + tok] = rt_diag(accx, lane);
+  xn[wave * 64 + lane] = rt_sumsq_total(x2p);   // (lane = lane group * 16 + tok)
 #pragma unroll
-    for (int i = 0; i < NWT; ++i) {
-      const int nt = i * TILES + tile;
-      if (nt < NT) wn[(ks * NT + nt) * 16 + tok] = rt_diag(accw[i], lane);
+  for (int i = 0; i < NWT; ++i) {
+    const int nt = i * TILES + tile;
+    if constexpr (L::WNG == 4) {
+      if (nt < NT) wn[(ks * NT + nt) * 64 + lane] = rt_sumsq_total(w2p[i]);
+    } else {
+      float v = rt_sumsq_total(w2p[i]);
+      v += __shfl_xor(v, 16);
+      v += __shfl_xor(v, 32);
+      if (nt < NT && lane < 16) wn[(ks * NT + nt) * 16 + tok] = v;
     }
   }
   for (int i = threadIdx.x; i < TILES * 16; i += RT_THREADS) ccount[i] = 0;
@@ -960,12 +972,16 @@ __global__ __launch_bounds__(RT_THREADS, (RouteTileLds<NT, TILES>::TOTAL <= 80 *
   for (int e = lane; e < NT * 16; e += MOE_WAVE) {
     float v = 0.f;
 #pragma unroll
-    for (int sl = 0; sl < KS; ++sl) v += wn[sl * NT * 16 + e];
+    for (int sl = 0; sl < KS; ++sl)
+#pragma unroll
+      for (int g = 0; g < L::WNG; ++g) v += wn[((sl * NT + (e >> 4)) * L::WNG + g) * 16 + (e & 15)];
     w2 = fmaxf(w2, v);
   }
-  w2 = wave_max(w2);
+  w2 = wave_max_dpp(w2);
 #pragma unroll
-  for (int sl = 0; sl < KS; ++sl) x2 += xn[(sl * TILES + tile) * 16 + trow];
+  for (int sl = 0; sl < KS; ++sl)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) x2 += xn[((sl * TILES + tile) * 4 + g) * 16 + trow];
   const float bnd = sqrtf(x2 * w2);
   float* picks = reinterpret_cast<float*>(smem + L::PICKS) + wave * 2 * (RT_KSEL + 1) * 16;
   select_tile<S, LPT>(s, bnd, true, t_ok, E, k, renorm, t, row, picks, cand_all + row * RT_CMAX,
@@ -1042,7 +1058,7 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     const uint4* __restrict__ x, const uint4* __restrict__ wg, const float* __restrict__ bias, int T,
     int d, int E, float* __restrict__ scores, float* __restrict__ norms) {
   __shared__ float part[RT_NW][RT_TM][16 * GNT];
-  __shared__ float xn[RT_NW][RT_TM], wn[RT_NW][16 * GNT];
+  __shared__ float xn[RT_NW * 4][RT_TM], wn[RT_NW * 4][16 * GNT];
   const int lane = lane_id();
   const int wave = threadIdx.x / MOE_WAVE;
   const int t0 = blockIdx.x * RT_TM, e0 = blockIdx.y * (16 * GNT);
@@ -1051,12 +1067,12 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
   const int kq = lane >> 4;  // which 8-element group of the 32-wide MFMA step
   const uint4* xrow = x + static_cast<int64_t>(min(t0 + r, T - 1)) * row16;
   const uint4* wrow[GNT];
-  f32x4_t acc[GNT], accw[GNT];
-  f32x4_t accx = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  f32x4_t acc[GNT];
+  RtSumSq x2, w2[GNT];
 #pragma unroll
   for (int nt = 0; nt < GNT; ++nt) {
     wrow[nt] = wg + static_cast<int64_t>(min(e0 + nt * 16 + r, E - 1)) * row16;
-    acc[nt] = accw[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    acc[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
   const int cw = ((row16 + RT_NW * 4 - 1) / (RT_NW * 4)) * 4;  // 16 B chunks per wave
   const int c0 = wave * cw;
@@ -1075,11 +1091,11 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
       if (cb + 4 * u < c1) {                         // wave-uniform
         uint4 av = a[u];
         if (cb + 4 * u + kq >= row16) av = make_uint4(0, 0, 0, 0);
-        accx = rt_mfma(av, av, accx);
+        rt_sumsq(av, x2);
 #pragma unroll
         for (int nt = 0; nt < GNT; ++nt) {
           acc[nt] = rt_mfma(av, b[u][nt], acc[nt]);
-          accw[nt] = rt_mfma(b[u][nt], b[u][nt], accw[nt]);   // (past the end: see route_kernel)
+          rt_sumsq(b[u][nt], w2[nt]);                       // (past the end: see route_kernel)
         }
       }
     }
@@ -1089,11 +1105,9 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
   for (int nt = 0; nt < GNT; ++nt)
 #pragma unroll
     for (int v = 0; v < 4; ++v) part[wave][4 * kq + v][nt * 16 + r] = acc[nt][v];
-  if (rt_diag_lane(lane)) {
-    xn[wave][r] = rt_diag(accx, lane);
+  xn[wave * 4 + kq][r] = rt_sumsq_total(x2);
 #pragma unroll
-    for (int nt = 0; nt < GNT; ++nt) wn[wave][nt * 16 + r] = rt_diag(accw[nt], lane);
-  }
+  for (int nt = 0; nt < GNT; ++nt) wn[wave * 4 + kq][nt * 16 + r] = rt_sumsq_total(w2[nt]);
   __syncthreads();
   // |x_t|^2 from the blocks of the first expert tile, |w_e|^2 from those of the first token tile
   {
@@ -1101,14 +1115,14 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
     if (blockIdx.y == 0 && i < RT_TM && t0 + i < T) {
       float v = 0.f;
 #pragma unroll
-      for (int w = 0; w < RT_NW; ++w) v += xn[w][i];
+      for (int w = 0; w < RT_NW * 4; ++w) v += xn[w][i];
       norms[t0 + i] = v;
     }
     const int ee = i - MOE_WAVE;
     if (blockIdx.x == 0 && ee >= 0 && ee < 16 * GNT && e0 + ee < E) {
       float v = 0.f;
 #pragma unroll
-      for (int w = 0; w < RT_NW; ++w) v += wn[w][ee];
+      for (int w = 0; w < RT_NW * 4; ++w) v += wn[w][ee];
       norms[T + e0 + ee] = v;
     }
   }
@@ -1128,10 +1142,11 @@ __global__ __launch_bounds__(RT_THREADS) void gate_tile_kernel(
 
 static size_t route_lds_bytes(int E) {
   const size_t dn = E > RT_CMAX ? E : RT_CMAX;
-  size_t ep = 16;                      // 16 NT of the kernel that serves E experts
-  while (ep < static_cast<size_t>(E)) ep <<= 1;
+  size_t ep = 16;                      // entries of a |w_e|^2 row in the kernel that serves E experts:
+  while (ep < static_cast<size_t>(E)) ep <<= 1;   // 16 NT, or 4 NT from 128 experts on (grouped)
+  if (ep >= 128) ep /= 4;
   return static_cast<size_t>(RT_NW) * RT_TM * E * 4 + RT_NW * dn * 8 +
-         RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int) + RT_NW * (RT_TM + ep) * sizeof(float);
+         RT_TM * RT_CMAX * sizeof(int) + RT_TM * sizeof(int) + RT_NW * 4 * (RT_TM + ep) * sizeof(float);
 }
 
 template <bool BF16, int NT, int RPW, bool PRE>
