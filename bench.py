@@ -372,6 +372,10 @@ def main():
         four_call = {"ms_per_step": ms4, "tokens_per_s": cfg.T / (ms4 * 1e-3), "per_call_ms": calls4["avg"],
                      "calls": "moe_route_ws, moe_count_and_permute (maps + x_perm rows), moe_grouped_ffn, "
                               "moe_combine"}
+        if cfg.dtype == si.BF16:
+            w4 = algorithmic_work(cfg)
+            four_call["ffn_pct_of_bf16_mfma_peak"] = 100.0 * (w4["ffn_up_flops"] + w4["ffn_down_flops"]) / (
+                (calls4["avg"]["ffn_up"] + calls4["avg"]["ffn_down"]) * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS
 
     # layers with one expert per token: the combine folded into the down-projection's store
     k1_form = None
