@@ -327,6 +327,23 @@ def test_route_ws_without_usable_workspace_is_plain_route():
     assert np.all(np.abs(host(w) - rw) <= 1e-5 * np.abs(rw) + 1e-9)
 
 
+def test_route_ws_with_room_for_the_scores_but_not_the_norms_is_plain_route():
+    # the two-kernel form needs T*E scores and T + E norms: a workspace of exactly T*E*4 bytes is
+    # not enough for it, and the call must behave like moe_route
+    cfg = si.small_config(T=48, d=2048, E=128, k=8, F=64)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    ridx, rw, _ = orc.route(L["x"], L["w_gate"], cfg.k, cfg.renorm, None)
+    idx = torch.full((cfg.T, cfg.k), -1, dtype=torch.int32, device="cuda")
+    w = torch.zeros((cfg.T, cfg.k), dtype=torch.float32, device="cuda")
+    nb = cfg.T * cfg.E * 4
+    ws = torch.full((nb + 256,), 0x5A, dtype=torch.uint8, device="cuda")
+    B.moe_route_ws(shape_of(cfg), dev(L["x"]), dev(L["w_gate"]), None, idx, w, None, ws, nb)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(idx), ridx)
+    assert np.all(np.abs(host(w) - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+    assert bool((ws[nb:] == 0x5A).all())            # nothing written past the size it was given
+
+
 # ----------------------------------------------------------------------------- count + permute
 def gpu_dispatch(cfg, x, idx):
     T, E, k, d = cfg.T, cfg.E, cfg.k, cfg.d
