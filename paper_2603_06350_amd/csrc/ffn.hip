@@ -210,9 +210,17 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   tc.e = e;
   tc.n_tile = loc / m_tiles;
   if (p.mode == TILES_EVEN) {
+    // The segment's 16-row sub-tiles are dealt in pairs: a tile's sub-tiles go to four wave rows,
+    // and wave rows 0, 2 and 1, 3 share their SIMDs, so a tile with an odd number of sub-tiles is
+    // as slow as one with the next even number.  67 sub-tiles become 17, 16, 16, 18 (9 + 8 + 8 + 9
+    // per SIMD pair), not 16, 17, 17, 17 (8 + 9 + 9 + 9).  An odd one out goes to the first tile,
+    // which has the fewest pairs (so no tile exceeds 20 sub-tiles).
     const int sub = (seg_end - seg_begin + 15) / 16;
-    tc.m_begin = seg_begin + (m_idx * sub / m_tiles) * 16;
-    tc.m_end = min(seg_end, seg_begin + ((m_idx + 1) * sub / m_tiles) * 16);
+    const int pairs = sub >> 1, odd = sub & 1;
+    const int b0 = m_idx == 0 ? 0 : 2 * (m_idx * pairs / m_tiles) + odd;
+    const int b1 = 2 * ((m_idx + 1) * pairs / m_tiles) + odd;
+    tc.m_begin = seg_begin + b0 * 16;
+    tc.m_end = min(seg_end, seg_begin + b1 * 16);
   } else {
     tc.m_begin = seg_begin + m_idx * bm;
     tc.m_end = min(seg_end, tc.m_begin + bm);
