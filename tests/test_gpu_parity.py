@@ -522,10 +522,10 @@ def test_grouped_ffn_even_tiles_every_wave_share(rows):
 
 SPLIT_CASES = [
     # (shape, whether some tile must have been split); a GEMM is eligible from K = 6144 on
-    (dict(T=600, d=1024, E=2, k=1, F=6144), True),    # main tiles, down-projection cut in 4
+    (dict(T=600, d=1024, E=2, k=1, F=6144), True),    # even tiles, down-projection cut in 4
     (dict(T=64, d=1024, E=4, k=2, F=6144), True),     # 64-row tiles only (32 rows per expert)
     (dict(T=600, d=6144, E=2, k=1, F=256), True),     # up-projection (gated) cut in 4
-    (dict(T=700, d=1024, E=2, k=1, F=6144, seed=11), None),   # remainders beside the main tiles
+    (dict(T=700, d=1024, E=2, k=1, F=6144, seed=11), None),   # 350 rows per expert: two even tiles of 176 rows each
     (dict(T=300, d=1024, E=2, k=1, F=2048), False),   # reductions too short: exactly the plain call
 ]
 
