@@ -206,3 +206,64 @@ def test_full_size_full_oracle(name):
         got = orc.to_f64(layer.to_host(getattr(buf, n)))
         err = np.abs(got - ref[n]).max() / np.abs(ref[n]).max()
         assert err <= tol, f"{n}: {err:.3e}"
+
+
+def test_large_batch_route_permute_combine():
+    """The bandwidth-bound batch on which bench.py times moe_route_ws, moe_count_and_permute and
+    moe_combine one by one (same shape, seed, entry points and workspace): routing and the
+    permutation against the full oracle on every token, the copied rows bit for bit, and the
+    combine (with the permuted activations standing in for the expert outputs, as in bench.py) on
+    sampled tokens and by what holds for every token."""
+    import bench
+    T, d, E, k = (bench.HBM_BOUND_SHAPE[n] for n in "TdEk")
+    cfg = si.small_config("hbm_bound", T=T, d=d, E=E, k=k, F=64, dtype=si.BF16, renorm=1, seed=8008)
+    print("generating", flush=True)
+    L = si.make_layer(cfg, parts=("x", "w_gate"))
+    st = torch.cuda.current_stream()
+    sh = B.make_shape(T, d, E, k, 64, B.MOE_BF16, 1)
+    A = T * k
+    ws_bytes = B.moe_workspace_bytes(sh)
+    kw = dict(device="cuda")
+    x, wg = layer.to_device(L["x"]), layer.to_device(L["w_gate"])
+    topk_idx = torch.empty((T, k), dtype=torch.int32, **kw)
+    topk_w = torch.empty((T, k), dtype=torch.float32, **kw)
+    counts = torch.empty((E,), dtype=torch.int32, **kw)
+    offsets = torch.empty((E + 1,), dtype=torch.int32, **kw)
+    dst_row = torch.empty((A,), dtype=torch.int32, **kw)
+    src_assign = torch.empty((A,), dtype=torch.int32, **kw)
+    x_perm = torch.zeros((A, d), dtype=torch.bfloat16, **kw)
+    y = torch.zeros((T, d), dtype=torch.bfloat16, **kw)
+    ws = torch.empty((ws_bytes,), dtype=torch.uint8, **kw)
+    print("running the three calls", flush=True)
+    B.moe_route_ws(sh, x, wg, None, topk_idx, topk_w, None, ws, ws_bytes, st)
+    B.moe_count_and_permute(sh, x, topk_idx, counts, offsets, dst_row, src_assign, x_perm, ws,
+                            ws_bytes, st)
+    B.moe_combine(sh, x_perm, dst_row, topk_w, y, st)
+    torch.cuda.synchronize()
+    print("oracle routing", flush=True)
+    ridx, rw, _ = orc.route(L["x"], L["w_gate"], k, 1)
+    bad = np.nonzero((layer.to_host(topk_idx) != ridx).any(axis=1))[0]
+    assert bad.size == 0, f"top-k differs on {bad.size} rows, first {bad[:5]}"
+    w = layer.to_host(topk_w)
+    assert np.all(np.abs(w - rw) <= 1e-5 * np.abs(rw) + 1e-9)
+    print("oracle permutation", flush=True)
+    rc, ro = orc.expert_load(ridx, E)
+    rd, rs = orc.permutation(ridx, E)
+    assert np.array_equal(layer.to_host(counts), rc)
+    assert np.array_equal(layer.to_host(offsets), ro)
+    assert np.array_equal(layer.to_host(dst_row), rd)
+    assert np.array_equal(layer.to_host(src_assign), rs)
+    xp = layer.to_host(x_perm)
+    assert np.array_equal(xp[rd], np.repeat(L["x"], k, axis=0))
+    print("oracle combine on sampled tokens", flush=True)
+    rng = np.random.default_rng(3)
+    toks = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, size=512)]))
+    rows = rd.reshape(T, k)[toks].reshape(-1)
+    y_ref = orc.combine(xp[rows], np.arange(rows.size, dtype=np.int32), rw[toks])
+    y_gpu = orc.to_f64(layer.to_host(y[torch.from_numpy(toks.astype(np.int64)).cuda()]))
+    # fp32 accumulation of k products, one rounding to bf16 on the store
+    assert np.all(np.abs(y_gpu - y_ref) <= 2.0 ** -8 * np.abs(y_ref) + 1e-30)
+    # for every token: its k permuted rows are copies of x[t] and its weights sum to one, so
+    # y[t] is x[t] up to the rounding of the weights' sum and of the store
+    yf, xf = y.float(), x.float()
+    assert bool((yf - xf).abs().le(2.0 ** -7 * xf.abs() + 1e-30).all())
