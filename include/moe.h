@@ -139,6 +139,10 @@ int moe_count_and_permute_static(const moe_shape_t* shape, const void* x, const 
  * x_perm [T*k,d]; w1, w3 [E,F,d]; w2 [E,d,F]; h [T*k,F] (caller-provided scratch,
  * holds the activations on return); y_perm [T*k,d]; all in `dtype`; offsets [E+1]
  * int32 on the device (read by the kernels; no host round trip).
+ * A GEMM's tiles run in rounds of the chip's compute units; when the last round is at most half
+ * full, the bf16 MFMA kernels cut each of its tiles along the rows into 2 to 4 pieces (of 64 rows
+ * or more) for the otherwise idle units.  A row's sums do not depend on the rows it shares a tile
+ * with, so the outputs are the same bits whether tiles are cut or not.
  * Two launches (one per GEMM) on `hip_stream`; the library keeps no stream, event or other state
  * of its own, so calls from several host threads or on several streams are independent, and a
  * stream capture records exactly these launches.
@@ -203,10 +207,15 @@ int moe_grouped_ffn_combine_k1(const moe_shape_t* shape, const void* x, const in
  * a small launch right after the GEMM adds them in part order (deterministic), rounds and stores
  * once.  For such tiles the fp32 sum is grouped differently than in the calls without a
  * workspace, so h and y_perm may differ from theirs in the last bit; all other rows are
- * bit-identical.  Each GEMM costs one more (mostly empty) launch.
+ * bit-identical.  Each GEMM costs one more (mostly empty) launch.  GEMMs whose reduction is too
+ * short to be worth cutting (fewer than 96 steps of 64) keep the cut along the rows of the calls
+ * without a workspace.
  *   x, src_assign   src_assign == NULL: x is x_perm [T*k, d] as for moe_grouped_ffn;
  *                   otherwise x [T, d] and the map, as for moe_grouped_ffn_gather
- *   parts           1 = up-projection only, 2 = down-projection only, 3 = both
+ *   parts           1 = up-projection only, 2 = down-projection only, 3 = both; plus 4: tiles
+ *                   of an under-filled last round are not cut along their rows either (every
+ *                   tile whole, as for a batch that fills its rounds: for measurements and for
+ *                   tests of the whole-tile code on small inputs; same output bits)
  *   workspace       device memory, 16-byte aligned, at least moe_ffn_workspace_bytes() bytes
  *                   (80 MiB on a 256-CU device), contents irrelevant; or NULL (then exactly
  *                   moe_grouped_ffn / moe_grouped_ffn_gather).  Calls that share a workspace

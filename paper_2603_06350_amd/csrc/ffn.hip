@@ -77,6 +77,9 @@ struct GemmArgs {
   const int32_t* out_map;
   const float* out_scale;
   int out_rows;     // rows of `out` (mapped row numbers are clamped to it)
+  // TILES_EVEN launches without split_ws: tiles of a last round that is at most half full are cut
+  // along their rows into pieces for the idle units (the grid has a round of extra blocks).
+  int m_split;
 };
 
 constexpr int SPLIT_SLOT_FLOATS = 320 * 256;   // one partial tile (the largest: 320 x 256 fp32)
@@ -96,6 +99,7 @@ struct TileCoord {
   int part, nparts;
   int pslot;   // partial-tile slot of this part; the parts of a tile have consecutive slots
 };
+constexpr int MSPLIT_MAX_PIECES = 4;
 
 // Inclusive prefix sum over the wave by DPP: four shifted adds inside each row of 16 lanes, then
 // the totals of rows 0 and 2 go to rows 1 and 3, and the total of rows 0-1 to rows 2 and 3.
@@ -152,6 +156,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   tc.part = 0;
   tc.nparts = 1;
   tc.pslot = 0;
+  int m_pieces = 1, m_piece = 0;
   if (SPLIT && p.split_ws) {
     // The tiles of an XCD's range run in rounds of its compute units.  If the last round is at
     // most half full, its tiles are cut along K into as many parts as fit the idle units (every
@@ -178,6 +183,24 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
       tc.part = j - t_local * parts;
       tc.nparts = parts;
       tc.pslot = xcd * cus_x + j;                // j < tail_x * parts <= cus_x
+    }
+    if (vid >= total) return false;
+  } else if (p.m_split && slot + max(1, (p.n_cu > 0 ? p.n_cu : 256) / 8) >= per_xcd) {
+    // No workspace: the tiles of a last round that is at most half full are cut along their rows
+    // instead, each piece a tile of its own that streams the whole weight tile (out of the L2, which
+    // its sister pieces fill at the same time).  The outputs are the same bits: a row's sums do not
+    // depend on which rows share its tile.  (Only blocks of the last two rounds come here: the
+    // integer divisions below cost a tile of the rounds before them half a percent of its time.)
+    const int cus_x = max(1, (p.n_cu > 0 ? p.n_cu : 256) / 8);
+    const int full_x = per_xcd / cus_x * cus_x;
+    const int tail_x = per_xcd - full_x;
+    if (slot >= full_x) {
+      if (tail_x > 0 && 2 * tail_x <= cus_x) m_pieces = min(cus_x / tail_x, MSPLIT_MAX_PIECES);
+      const int j = slot - full_x;
+      const int t_local = j / m_pieces;
+      if (t_local >= tail_x) return false;
+      vid = xcd * per_xcd + full_x + t_local;
+      m_piece = j - t_local * m_pieces;
     }
     if (vid >= total) return false;
   } else if (slot >= per_xcd || vid >= total) {
@@ -219,8 +242,16 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
     const int pairs = sub >> 1, odd = sub & 1;
     const int b0 = m_idx == 0 ? 0 : 2 * (m_idx * pairs / m_tiles) + odd;
     const int b1 = 2 * ((m_idx + 1) * pairs / m_tiles) + odd;
-    tc.m_begin = seg_begin + b0 * 16;
-    tc.m_end = min(seg_end, seg_begin + b1 * 16);
+    int s0 = b0, s1 = b1;
+    if (m_pieces > 1) {
+      const int n_sub = b1 - b0;
+      const int pieces = min(m_pieces, max(1, n_sub / 4));    // a piece keeps 64 rows or more
+      if (m_piece >= pieces) return false;
+      s0 = b0 + m_piece * n_sub / pieces;
+      s1 = b0 + (m_piece + 1) * n_sub / pieces;
+    }
+    tc.m_begin = seg_begin + s0 * 16;
+    tc.m_end = min(seg_end, seg_begin + s1 * 16);
   } else {
     tc.m_begin = seg_begin + m_idx * bm;
     tc.m_end = min(seg_end, tc.m_begin + bm);
@@ -1040,7 +1071,7 @@ static int launch_grouped_gemm(GemmArgs a, int mode, int bm, int64_t A, int thre
   if (grid == 0) return MOE_OK;
   grid = (grid + 7) / 8 * 8;
   const int cu8 = (a.n_cu > 0 ? a.n_cu : 256) / 8 * 8;
-  if (sum_kernel) grid += cu8;
+  if (sum_kernel || a.m_split) grid += cu8;
   if (grid > 0x7FFFFFFF) return MOE_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(main_kernel, dim3(static_cast<unsigned>(grid)), dim3(threads), lds_bytes, st, a);
   int rc = launch_status();
@@ -1055,12 +1086,14 @@ static int launch_grouped_gemm(GemmArgs a, int mode, int bm, int64_t A, int thre
 }
 
 template <bool GATED, bool ALTERNATE>
-static int launch_even(const GemmArgs& a, int64_t A, hipStream_t st) {
+static int launch_even(const GemmArgs& a, int64_t A, bool row_split, hipStream_t st) {
   static LdsOnce once[2], once_sum;
   if (a.split_ws && a.K >= SPLIT_MIN_K)
     return launch_grouped_gemm(a, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, true, ALTERNATE>,
                                once[1], ffn_even_sum_parts_kernel<GATED>, once_sum, st);
-  return launch_grouped_gemm(a, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, false, ALTERNATE>,
+  GemmArgs b = a;
+  b.m_split = row_split ? 1 : 0;
+  return launch_grouped_gemm(b, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, false, ALTERNATE>,
                              once[0], nullptr, once_sum, st);
 }
 
@@ -1097,7 +1130,8 @@ constexpr int EVEN_MIN_ROWS = 128;
 constexpr int ALTERNATE_MIN_ROWS = 384;
 
 // Both GEMMs (or one of them) on the MFMA path: one launch each on the caller's stream.
-static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, hipStream_t st) {
+static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, bool row_split,
+                    hipStream_t st) {
   int rc = MOE_OK;
   if (A / g1.E < EVEN_MIN_ROWS) {
     // Few rows per expert (decode, small prefill batches): the call is bound by streaming each
@@ -1111,11 +1145,11 @@ static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, hip
     return rc;
   }
   if (A / g1.E >= ALTERNATE_MIN_ROWS) {
-    if (up && (rc = launch_even<true, true>(g1, A, st)) != MOE_OK) return rc;
-    if (down) rc = launch_even<false, true>(g2, A, st);
+    if (up && (rc = launch_even<true, true>(g1, A, row_split, st)) != MOE_OK) return rc;
+    if (down) rc = launch_even<false, true>(g2, A, row_split, st);
   } else {
-    if (up && (rc = launch_even<true, false>(g1, A, st)) != MOE_OK) return rc;
-    if (down) rc = launch_even<false, false>(g2, A, st);
+    if (up && (rc = launch_even<true, false>(g1, A, row_split, st)) != MOE_OK) return rc;
+    if (down) rc = launch_even<false, false>(g2, A, row_split, st);
   }
   return rc;
 }
@@ -1127,7 +1161,8 @@ static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, hip
 static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const int32_t* src_assign,
                             const int32_t* offsets, const void* w1, const void* w3, const void* w2,
                             void* h, void* y_perm, int parts, void* hip_stream,
-                            void* split_ws = nullptr, const float* combine_w = nullptr) {
+                            void* split_ws = nullptr, const float* combine_w = nullptr,
+                            bool row_split = true) {
   int rc = check_shape(shape);
   if (rc != MOE_OK) return rc;
   if (shape->T == 0) return MOE_OK;
@@ -1153,7 +1188,7 @@ static int grouped_ffn_impl(const moe_shape_t* shape, const void* x_perm, const 
   if (shape->dtype == MOE_BF16 && d % 64 == 0 && F % 64 == 0) {
     g1.n_tiles = (F + 127) / 128;
     g2.n_tiles = (d + 255) / 256;
-    return mfma_ffn(g1, g2, up, down, A, st);
+    return mfma_ffn(g1, g2, up, down, A, row_split, st);
   }
   g1.n_tiles = (F + 63) / 64;
   g2.n_tiles = (d + 63) / 64;
@@ -1200,13 +1235,15 @@ extern "C" int moe_grouped_ffn_ws(const moe_shape_t* shape, const void* x, const
                                   const int32_t* offsets, const void* w1, const void* w3,
                                   const void* w2, void* h, void* y_perm, int parts, void* workspace,
                                   size_t workspace_bytes, void* hip_stream) {
+  const bool whole_tiles = (parts & 4) != 0;
+  parts &= ~4;
   if (parts < 1 || parts > 3) return MOE_ERR_INVALID_ARG;
   if (workspace) {
     if (!moe::aligned16(workspace)) return MOE_ERR_INVALID_ARG;
     if (workspace_bytes < ffn_split_workspace_bytes()) return MOE_ERR_WORKSPACE;
   }
   return moe::grouped_ffn_impl(shape, x, src_assign, offsets, w1, w3, w2, h, y_perm, parts,
-                               hip_stream, workspace);
+                               hip_stream, workspace, nullptr, !whole_tiles);
 }
 
 extern "C" int moe_grouped_ffn_gather(const moe_shape_t* shape, const void* x,

@@ -151,7 +151,9 @@ def test_grouped_ffn_ws_validates_on_the_host(lib):
     args = (one, None, one, one, one, one, one, one)
     cases = [
         (lambda: B.moe_grouped_ffn_ws(sh, *args, 0, one, nb), -1),             # parts out of range
-        (lambda: B.moe_grouped_ffn_ws(sh, *args, 4, one, nb), -1),
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 4, one, nb), -1),             # the whole-tile flag alone
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 8, one, nb), -1),
+        (lambda: B.moe_grouped_ffn_ws(sh, *args, 11, one, nb), -1),
         (lambda: B.moe_grouped_ffn_ws(sh, *args, 3, one + 4, nb), -1),         # workspace misaligned
         (lambda: B.moe_grouped_ffn_ws(sh, *args, 3, one, nb - 1), -3),         # workspace too small
         (lambda: B.moe_grouped_ffn_ws(sh, None, None, one, one, one, one, one, one, 3, one, nb), -1),

@@ -62,6 +62,13 @@ def test_random_layer(cfg):
             scale = np.abs(ref[n]).max()
             err = np.abs(got - ref[n]).max() / (scale if scale > 0 else 1.0)
             assert err <= tol, (n, fused, err)
+        # the same call with every tile kept whole (inputs this small leave a round of tiles
+        # under-filled, whose tiles the call above cuts along their rows): the same bits
+        h, yp = torch.zeros_like(buf.h), torch.zeros_like(buf.y_perm)
+        B.moe_grouped_ffn_ws(buf.shape, args[0] if fused else buf.x_perm, buf.src_assign if fused else None,
+                             buf.offsets, args[2], args[3], args[4], h, yp, 3 | 4, None, 0)
+        torch.cuda.synchronize()
+        assert torch.equal(h, buf.h) and torch.equal(yp, buf.y_perm), fused
 
 
 def route_cases(n, seed):
