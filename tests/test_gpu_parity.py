@@ -529,6 +529,26 @@ def test_grouped_ffn_even_tiles_every_wave_share(rows):
         check_ffn(cfg, L, idx)
 
 
+ROUND_CASES = [
+    # (rows per expert, d, F): enough tiles for whole rounds of the chip's 256 compute units plus a
+    # last round that is under-filled (its tiles are cut along their rows), just over half full
+    # (left whole) or absent; every element of h and y_perm is compared
+    ([2048] * 8, 128, 640),                      # up 280 tiles (1 round + 24), down 56 (a fifth of a round)
+    ([1500] * 16, 512, 384),                     # up 240 (under a round, whole tiles), down 160
+    ([3000, 17, 0, 2500, 64, 700, 1, 4000, 0, 333, 2100, 65, 1290, 1280, 320, 321], 256, 1152),
+    ([1024] * 9, 1024, 512),                     # up 144, down 144: just over half a round, not cut
+    ([640] * 40, 128, 896),                      # up 560 (2 rounds + 48), down 80
+]
+
+
+@pytest.mark.parametrize("rows,d,F", ROUND_CASES, ids=lambda v: str(v) if isinstance(v, int) else f"E{len(v)}")
+def test_grouped_ffn_whole_rounds_and_under_filled_last_rounds(rows, d, F):
+    cfg = si.small_config(T=sum(rows), d=d, E=len(rows), k=1, F=F, seed=len(rows) + d + F)
+    L = si.make_layer(cfg)
+    idx = np.repeat(np.arange(len(rows), dtype=np.int32), rows).reshape(-1, 1)
+    check_ffn(cfg, L, idx)
+
+
 SPLIT_CASES = [
     # (shape, whether some tile must have been split); a GEMM is eligible from K = 6144 on
     (dict(T=600, d=1024, E=2, k=1, F=6144), True),    # even tiles, down-projection cut in 4
