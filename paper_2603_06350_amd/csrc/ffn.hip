@@ -98,8 +98,10 @@ struct TileCoord {
   // K split of a tile of the last, partial round (nparts == 1: the whole K range)
   int part, nparts;
   int pslot;   // partial-tile slot of this part; the parts of a tile have consecutive slots
+  int sharers; // tiles and pieces of tiles of this expert that read the same weight rows
 };
 constexpr int MSPLIT_MAX_PIECES = 4;
+constexpr int WGT_NT_MAX_SHARERS = 2;
 
 // Inclusive prefix sum over the wave by DPP: four shifted adds inside each row of 16 lanes, then
 // the totals of rows 0 and 2 go to rows 1 and 3, and the total of rows 0-1 to rows 2 and 3.
@@ -232,6 +234,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
   const int seg_end = min(__builtin_amdgcn_readlane(found_oe, src), p.rows);
   tc.e = e;
   tc.n_tile = loc / m_tiles;
+  tc.sharers = m_tiles;
   if (p.mode == TILES_EVEN) {
     // The segment's 16-row sub-tiles are dealt in pairs: a tile's sub-tiles go to four wave rows,
     // and wave rows 0, 2 and 1, 3 share their SIMDs, so a tile with an odd number of sub-tiles is
@@ -247,6 +250,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, TileCoord& tc) {
       const int n_sub = b1 - b0;
       const int pieces = min(m_pieces, max(1, n_sub / 4));    // a piece keeps 64 rows or more
       if (m_piece >= pieces) return false;
+      tc.sharers = m_tiles + pieces - 1;
       s0 = b0 + m_piece * n_sub / pieces;
       s1 = b0 + (m_piece + 1) * n_sub / pieces;
     }
@@ -472,12 +476,25 @@ __device__ __forceinline__ void ffn_ring_tile(const GemmArgs& p, const TileCoord
       __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(base_b0), 0, 0x7FFFFFFF, 0x00020000);
   const __amdgpu_buffer_rsrc_t rs_b1 = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<unsigned char*>(GATED ? base_b1 : base_b0), 0, 0x7FFFFFFF, 0x00020000);
+  // The weight rows of an expert that is this one tile are read once by the whole chip: requested
+  // with the non-temporal hint they do not displace what other blocks still share in the L2.
+  // (Measured with the hint on every ring tile: decode-shaped layer 0.79 -> 0.72 ms, Mixtral shape
+  // at 16 tokens 0.51 -> 0.48 ms, its weights then stream at 5.9 TB/s; with two tiles per expert,
+  // Mixtral shape at 256 and 448 tokens, 1 to 5 % slower, hence the condition.  Only in launches
+  // of ring tiles alone: for the small experts of a skewed batch, inside a launch of even tiles,
+  // the hint gained nothing measurable.)
+  const bool wgt_nt = p.mode == TILES_FIXED && tc.sharers <= 1;   // block-uniform
   // instruction i of stage kt into LDS stage `stage` (1 KiB per wave instruction)
   auto issue_load = [&](int i, int kt, int stage) {
     const __amdgpu_buffer_rsrc_t rs = (i < NLA) ? rs_a : (!GATED || i < NLA + NLB) ? rs_b0 : rs_b1;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(
-        rs, (__attribute__((address_space(3))) void*)(lds + stage * STAGE + (i * NW + wave) * 1024), 16,
-        static_cast<int>(soff[i]), kt * ROWB, 0, 0);
+    if (i < NLA || !wgt_nt)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rs, (__attribute__((address_space(3))) void*)(lds + stage * STAGE + (i * NW + wave) * 1024), 16,
+          static_cast<int>(soff[i]), kt * ROWB, 0, 0);
+    else
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(
+          rs, (__attribute__((address_space(3))) void*)(lds + stage * STAGE + (i * NW + wave) * 1024), 16,
+          static_cast<int>(soff[i]), kt * ROWB, 0, 2);             // aux bit 1: nt
   };
 
   // ---- LDS read addresses of the MFMA fragments ------------------------------------------------
@@ -644,7 +661,7 @@ __device__ __forceinline__ void even_wave_rows(int rows_valid, int wm, int& miv,
 // make a third weight buffer (160 KiB), and the weight rows are requested a stage earlier than the
 // activation rows: they are the operand that misses the L2 (an XCD's tiles share activation
 // rows far more often than weight rows), so their requests take longest to return.
-template <bool GATED, bool SPLIT, bool ALTERNATE, int MI>
+template <bool GATED, bool SPLIT, bool ALTERNATE, bool WNT, int MI>
 __device__ __forceinline__ void ffn_even_tile(const GemmArgs& p, const TileCoord& tc, unsigned char* lds) {
   constexpr int NW = 8, WN = 2;
   constexpr int BM = MI * 64, NI = 8;
@@ -723,8 +740,17 @@ __device__ __forceinline__ void ffn_even_tile(const GemmArgs& p, const TileCoord
   // last n-tile of a matrix whose row count is not a multiple of the tile) re-reads the tile's
   // first rows; its products are never stored.
   constexpr int W_LOADS = 32 / ns;
-  auto issue_wgt = [&](int kt, int wb) {
-    if (alternate && lset != ((kt + NWB) & 1)) return;
+  // WNT: weight rows that at most two tiles read (an expert of one or two tiles) are requested with
+  // the non-temporal hint: nothing will ask for them again, and they stop displacing the activation
+  // rows, which the other n-tiles of the round and the later rounds re-read, from the L2.  Weight
+  // rows shared by more tiles keep the default policy (measured with the hint on every tile: the
+  // Mixtral shape, four tiles per expert, up-projection 4 % slower; llama4 and phi shapes, one and
+  // two tiles per expert, both GEMMs 4 to 7 % faster).  The branch per stage costs a launch whose
+  // tiles all keep the default policy about 1 %, so the host builds it in (WNT) only for calls with
+  // few rows per expert.
+  const bool wgt_nt = WNT && tc.sharers <= WGT_NT_MAX_SHARERS;       // block-uniform
+  auto issue_wgt_with = [&](int kt, int wb, auto aux_c) {
+    constexpr int AUX = decltype(aux_c)::value;
 #pragma unroll
     for (int i = 0; i < W_LOADS; ++i) {
       // group i * ns + lw of the 32 weight row groups; gated: groups 0-15 are W1 rows 0-127 of the
@@ -735,12 +761,19 @@ __device__ __forceinline__ void ffn_even_tile(const GemmArgs& p, const TileCoord
       if (!GATED || g0 < 128)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rs_b0, (__attribute__((address_space(3))) void*)(lds + W_BASE + wb * EVEN_WGT + (i * ns + lw) * 1024),
-            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
+            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, AUX);
       else
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             rs_b1, (__attribute__((address_space(3))) void*)(lds + W_BASE + wb * EVEN_WGT + (i * ns + lw) * 1024),
-            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, 0);
+            16, static_cast<int>(soff_w), kt * ROWB + jr * K * 2, 0, AUX);
     }
+  };
+  auto issue_wgt = [&](int kt, int wb) {
+    if (alternate && lset != ((kt + NWB) & 1)) return;
+    if (wgt_nt)
+      issue_wgt_with(kt, wb, std::integral_constant<int, 2>{});    // aux bit 1: nt
+    else
+      issue_wgt_with(kt, wb, std::integral_constant<int, 0>{});
   };
 
   // ---- LDS addresses of this lane's fragments per k-step.  A lane holds, for row lane%16 of a
@@ -902,7 +935,7 @@ __device__ __forceinline__ void ffn_even_tile(const GemmArgs& p, const TileCoord
 // long, 1 % slower, so it keeps two weight buffers for every tile.)
 constexpr int EVEN_ROWS_3WB = 256;
 
-template <bool GATED, bool SPLIT, bool ALTERNATE>
+template <bool GATED, bool SPLIT, bool ALTERNATE, bool WNT>
 __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   extern __shared__ __align__(1024) unsigned char lds[];
   TileCoord tc;
@@ -911,9 +944,9 @@ __global__ __launch_bounds__(512) void ffn_even_kernel(GemmArgs p) {
   if (rows <= RING_ROWS)
     ffn_ring_tile<RING_ROWS, GATED, 2, 4, 4, SPLIT>(p, tc, lds);
   else if (!GATED && rows <= EVEN_ROWS_3WB)
-    ffn_even_tile<GATED, SPLIT, ALTERNATE, 4>(p, tc, lds);
+    ffn_even_tile<GATED, SPLIT, ALTERNATE, WNT, 4>(p, tc, lds);
   else
-    ffn_even_tile<GATED, SPLIT, ALTERNATE, 5>(p, tc, lds);
+    ffn_even_tile<GATED, SPLIT, ALTERNATE, WNT, 5>(p, tc, lds);
 }
 
 // The launch after ffn_even_kernel<.., SPLIT>: adds the parts of every split tile and stores it.
@@ -1085,15 +1118,15 @@ static int launch_grouped_gemm(GemmArgs a, int mode, int bm, int64_t A, int thre
   return rc;
 }
 
-template <bool GATED, bool ALTERNATE>
+template <bool GATED, bool ALTERNATE, bool WNT>
 static int launch_even(const GemmArgs& a, int64_t A, bool row_split, hipStream_t st) {
   static LdsOnce once[2], once_sum;
   if (a.split_ws && a.K >= SPLIT_MIN_K)
-    return launch_grouped_gemm(a, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, true, ALTERNATE>,
+    return launch_grouped_gemm(a, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, true, ALTERNATE, WNT>,
                                once[1], ffn_even_sum_parts_kernel<GATED>, once_sum, st);
   GemmArgs b = a;
   b.m_split = row_split ? 1 : 0;
-  return launch_grouped_gemm(b, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, false, ALTERNATE>,
+  return launch_grouped_gemm(b, TILES_EVEN, EVEN_BM, A, 512, EVEN_LDS, ffn_even_kernel<GATED, false, ALTERNATE, WNT>,
                              once[0], nullptr, once_sum, st);
 }
 
@@ -1128,6 +1161,9 @@ static int launch_generic(GemmArgs a, int64_t A, hipStream_t st) {
 // slower at 256, where each expert is a single tile).
 constexpr int EVEN_MIN_ROWS = 128;
 constexpr int ALTERNATE_MIN_ROWS = 384;
+// Mean rows per expert below which the kernels are built with the per-tile choice of the
+// non-temporal hint for weight rows (experts of at most two tiles are then the rule).
+constexpr int WGT_NT_ROWS = 2 * EVEN_BM;
 
 // Both GEMMs (or one of them) on the MFMA path: one launch each on the caller's stream.
 static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, bool row_split,
@@ -1144,12 +1180,15 @@ static int mfma_ffn(GemmArgs g1, GemmArgs g2, bool up, bool down, int64_t A, boo
     if (down) rc = launch_ring<false>(g2, A, st);
     return rc;
   }
-  if (A / g1.E >= ALTERNATE_MIN_ROWS) {
-    if (up && (rc = launch_even<true, true>(g1, A, row_split, st)) != MOE_OK) return rc;
-    if (down) rc = launch_even<false, true>(g2, A, row_split, st);
+  if (A / g1.E >= WGT_NT_ROWS) {
+    if (up && (rc = launch_even<true, true, false>(g1, A, row_split, st)) != MOE_OK) return rc;
+    if (down) rc = launch_even<false, true, false>(g2, A, row_split, st);
+  } else if (A / g1.E >= ALTERNATE_MIN_ROWS) {
+    if (up && (rc = launch_even<true, true, true>(g1, A, row_split, st)) != MOE_OK) return rc;
+    if (down) rc = launch_even<false, true, true>(g2, A, row_split, st);
   } else {
-    if (up && (rc = launch_even<true, false>(g1, A, row_split, st)) != MOE_OK) return rc;
-    if (down) rc = launch_even<false, false>(g2, A, row_split, st);
+    if (up && (rc = launch_even<true, false, true>(g1, A, row_split, st)) != MOE_OK) return rc;
+    if (down) rc = launch_even<false, false, true>(g2, A, row_split, st);
   }
   return rc;
 }
